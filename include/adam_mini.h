@@ -1,0 +1,173 @@
+/*
+ * adam_mini.h -- C ABI of the MI355X (gfx950) Adam-mini optimizer-step library.
+ *
+ * What the library computes is one step of the paper's Algorithm 1 ("Adam-mini,
+ * general form", Section 2.3; repeated as Algorithm 2 in Appendix B) over a list
+ * of tensors.  For every block b of the parameter partition, with g the block's
+ * gradient, n_b its element count, t the 1-based step and
+ * bc1 = 1 - beta1^t, bc2 = 1 - beta2^t:
+ *
+ *     param_i <- param_i - lr * lambda_k * param_i            (decoupled decay)
+ *     m_i     <- (1 - beta1) * g_i + beta1 * m_i
+ *     v_b     <- (1 - beta2) * (sum_i g_i^2) / n_b + beta2 * v_b   (ONE scalar per block)
+ *     param_i <- param_i - (lr / bc1) * m_i / (sqrt(v_b / bc2) + eps)
+ *
+ * The partition (Algorithm 3, "Partition for Transformers", Appendix B: embedding
+ * and output layers by token, query/key by head, value / attention projection /
+ * MLP by output neuron, everything else as one block) always cuts a row-major
+ * tensor whose partition dimension is outermost into equal, contiguous runs of
+ * elements, so a tensor's partition is described by one number, block_numel.
+ * block_numel == 1 makes the step vanilla AdamW with a dense v (Section 2.3:
+ * Adam-mini replaces g*g of Adam by its block mean); block_numel == numel is the
+ * "Partition for non-Transformers" of Appendix B.
+ *
+ * Conventions
+ *   - Every pointer named *_dev / documented "device" is a HIP device pointer on
+ *     the layout's device; everything else is host memory.
+ *   - All functions return ADAM_MINI_OK (0) or a negative adam_mini_status code.
+ *     Nothing is thrown across the boundary.  Argument validation happens before
+ *     any kernel launch: on a validation error no device memory was touched.
+ *   - The library owns only the layout handle (host tables, device work tables,
+ *     partial-sum scratch).  The caller owns params, grads, exp_avg and v.
+ */
+#ifndef ADAM_MINI_H_
+#define ADAM_MINI_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum adam_mini_status {
+  ADAM_MINI_OK = 0,
+  ADAM_MINI_INVALID_ARG = -1,   /* null pointer, zero size, block_numel does not divide numel,
+                                   flags != 0, step == 0, beta outside [0,1), eps < 0,
+                                   non-finite hyper-parameter, unknown dtype, bad tensor index */
+  ADAM_MINI_MISALIGNED = -2,    /* a device base pointer is not 16-byte aligned */
+  ADAM_MINI_OUT_OF_MEMORY = -3, /* host or device allocation failed */
+  ADAM_MINI_HIP_ERROR = -4,     /* a HIP runtime call failed (see adam_mini_last_hip_error) */
+  ADAM_MINI_NO_DEVICE = -5      /* the layout was built with device < 0 (host-only layout) */
+} adam_mini_status;
+
+/* Gradient element type.  Params, exp_avg (m) and v are always fp32. */
+enum { ADAM_MINI_GRAD_F32 = 0, ADAM_MINI_GRAD_BF16 = 1 };
+
+/* Which kernel family serves a tensor (reported by adam_mini_export_layout). */
+enum {
+  ADAM_MINI_PATH_ELEMENTWISE = 0, /* block_numel == 1: AdamW-equivalent, dense v */
+  ADAM_MINI_PATH_ROW = 1,         /* whole block held in registers of <= one workgroup; single pass */
+  ADAM_MINI_PATH_LARGE = 2,       /* block spans several workgroups: partial sums, finalize, update */
+  ADAM_MINI_PATH_ROW_LDS = 3      /* whole block staged in one workgroup's LDS; single pass */
+};
+
+/*
+ * One tensor of the multi-tensor list.  The tensor is contiguous, row-major, with
+ * the partition dimension outermost; its blocks are elements
+ * [j*block_numel, (j+1)*block_numel), j = 0 .. numel/block_numel - 1.
+ *   rows of an [out,in] weight (value / attn.proj / mlp; embed / output by token): block_numel = in
+ *   heads of a [heads*head_dim, in] query / key weight:                            block_numel = head_dim*in
+ *   any other tensor (norm gains, biases):                                          block_numel = numel
+ *   AdamW-equivalent:                                                               block_numel = 1
+ */
+typedef struct adam_mini_tensor_desc {
+  uint64_t numel;       /* > 0 */
+  uint64_t block_numel; /* > 0 and divides numel */
+  float wd_scale;       /* lambda_k = weight_decay * wd_scale (1 for decayed tensors, 0 for none); finite, >= 0 */
+  uint32_t flags;       /* reserved, must be 0 */
+} adam_mini_tensor_desc;
+
+/* Hyper-parameters of one step (Algorithm 1, lines 1 and 5-10). */
+typedef struct adam_mini_hparams {
+  float lr;           /* eta_t, finite */
+  float beta1;        /* in [0,1) */
+  float beta2;        /* in [0,1) */
+  float eps;          /* >= 0 */
+  float weight_decay; /* lambda, finite */
+  uint64_t step;      /* t >= 1 (t = 0 would divide by 1 - beta^0 = 0) */
+} adam_mini_hparams;
+
+typedef struct adam_mini_layout adam_mini_layout; /* opaque */
+
+/*
+ * Build the block layout of a tensor list (Algorithm 3 realised as descriptors).
+ * Host-only work: validates the descriptors, assigns v indices (the v scalars of
+ * all tensors are stored back to back in tensor order: tensor k owns
+ * v[v_offset[k] .. v_offset[k+1]), v_offset = exclusive prefix sum of
+ * numel/block_numel), picks a kernel family per tensor and builds the work tables.
+ * No HIP call is made here; device tables and scratch are created by the first
+ * adam_mini_step / adam_mini_write_block_ids on `device`.
+ *   descs      host array [n_tensors], copied
+ *   grad_dtype ADAM_MINI_GRAD_F32 or ADAM_MINI_GRAD_BF16, same for all tensors
+ *   device     HIP device ordinal, or -1 for a host-only layout (export works, step does not)
+ *   out        receives the handle; free with adam_mini_destroy_layout
+ */
+int adam_mini_init_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors,
+                          int grad_dtype, int device, adam_mini_layout** out);
+
+/* Number of fp32 scalars the caller must provide in v (sum over tensors of
+ * numel/block_numel).  0 if layout is null. */
+uint64_t adam_mini_num_blocks(const adam_mini_layout* layout);
+
+/* Number of tensors of the layout (0 if null). */
+uint32_t adam_mini_num_tensors(const adam_mini_layout* layout);
+
+/*
+ * Copy out the integer layout.  v_offset: host array [n_tensors + 1] (may be null);
+ * path_kind: host array [n_tensors] of ADAM_MINI_PATH_* (may be null).
+ */
+int adam_mini_export_layout(const adam_mini_layout* layout, uint64_t* v_offset,
+                            uint32_t* path_kind);
+
+/* Host lookup: index into v used by element `elem` of tensor `tensor`, written to
+ * *out.  Same answer the device tables give (adam_mini_write_block_ids). */
+int adam_mini_block_id(const adam_mini_layout* layout, uint32_t tensor, uint64_t elem,
+                       uint64_t* out);
+
+/*
+ * Device check of the layout: for tensor `tensor`, every element's v index is
+ * written by walking the same device work tables, with the same work-item to
+ * element mapping, that adam_mini_step uses.  ids_dev: device array of numel
+ * uint64.  Asynchronous on hip_stream (a hipStream_t passed as void*; null = the
+ * default stream).  Used to compare the block-index layout bit for bit with an
+ * independent implementation.
+ */
+int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor,
+                              uint64_t* ids_dev, void* hip_stream);
+
+/*
+ * One optimizer step over all tensors (Algorithm 1 lines 3-11 for every block).
+ *   params   host array [n_tensors] of device pointers, fp32, updated in place
+ *   grads    host array [n_tensors] of device pointers, fp32 or bf16 per the layout; read only
+ *   exp_avg  host array [n_tensors] of device pointers, fp32 first moment m, updated in place
+ *   v_dev    device array of adam_mini_num_blocks() fp32, updated in place
+ *   hp       host pointer, read during the call
+ *   hip_stream  hipStream_t as void* (null = default stream); all work is enqueued there
+ * m and v must be zero before the first step (t = 1).  Every device pointer must be
+ * 16-byte aligned.  Tensors must not overlap each other.  The call is asynchronous
+ * and never allocates or synchronises, except that the first call on a layout, and
+ * any call whose three pointer lists differ from the previous call's, creates or
+ * re-uploads the device work tables and waits for that upload.  Results are
+ * bitwise reproducible: no atomics on floating-point data, fixed summation order.
+ * Concurrent calls on the same layout race on its scratch; use one layout per
+ * stream.  Non-finite gradients are not skipped: they propagate into the block's
+ * v and parameters (and no other block's).
+ */
+int adam_mini_step(adam_mini_layout* layout, void* const* params,
+                   const void* const* grads, void* const* exp_avg, float* v_dev,
+                   const adam_mini_hparams* hp, void* hip_stream);
+
+/* Frees host and device resources of the layout (null is a no-op).  The caller
+ * must make sure no step using the layout is still running. */
+void adam_mini_destroy_layout(adam_mini_layout* layout);
+
+/* Static description of a status code (never null). */
+const char* adam_mini_strerror(int status);
+
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char* adam_mini_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAM_MINI_H_ */

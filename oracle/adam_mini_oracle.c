@@ -1,0 +1,152 @@
+/*
+ * Adam-mini step oracle: test infrastructure, NOT part of the product.
+ *
+ * A plain, slow CPU statement of what one optimizer step computes, used only
+ * by the tests, the smoke check and the CPU-baseline leg of the benchmark.
+ * It shares no code with the HIP library and the HIP library never calls it.
+ *
+ * Arithmetic: everything in IEEE double.  State (param, m, v) is held in
+ * double between steps; gradients arrive as fp32 or bf16 bit patterns and are
+ * widened exactly.  Hyper-parameters arrive as doubles (the caller widens the
+ * same fp32 values the GPU library receives).
+ *
+ * Source of each formula: the paper's Algorithm 1 ("Adam-mini, general form",
+ * Section 2.3) which is repeated as Algorithm 2 in Appendix B.  Per block:
+ *     g      = grad of the block
+ *     param  = param - lr * lambda * param
+ *     m      = (1 - beta1) * g + beta1 * m
+ *     m_hat  = m / (1 - beta1^t)
+ *     v      = (1 - beta2) * mean(g .* g) + beta2 * v      (one scalar per block)
+ *     v_hat  = v / (1 - beta2^t)
+ *     param  = param - lr * m_hat / (sqrt(v_hat) + eps)
+ * The blocks of one tensor are the consecutive, equally sized, contiguous runs
+ * of `block_numel` elements of the row-major tensor: that is what "partition
+ * by tokens / heads / output neurons" (Algorithm 3, Appendix B) yields when the
+ * partition dimension is the outermost one.  block_numel == 1 is vanilla AdamW
+ * (Section 2.3, "replaces g.*g in vanilla Adam by its mean value"); block_numel
+ * == numel is the non-Transformer partition (Algorithm "Partition for
+ * non-Transformers", Appendix B).
+ *
+ * Pins (tests/test_oracle_pins.py): AdamW special case against a library
+ * routine, constant-gradient closed form, EMA identity, hand-worked rational
+ * example, brute force against a dictionary-of-slices transcription of the
+ * partition, symmetries, layout invariants.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+#define AMO_GRAD_F32 0
+#define AMO_GRAD_BF16 1
+#define AMO_GRAD_F64 2
+
+/* Exact widening of one gradient element to double. */
+static double amo_grad_at(const void *g, int dtype, uint64_t i) {
+  if (dtype == AMO_GRAD_F32) {
+    return (double)((const float *)g)[i];
+  } else if (dtype == AMO_GRAD_BF16) {
+    /* bf16 is the upper half of an fp32 word */
+    uint32_t bits = ((uint32_t)((const uint16_t *)g)[i]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+  }
+  return ((const double *)g)[i];
+}
+
+/*
+ * One step of Algorithm 1 on ONE block of n elements.
+ *   p, m : n doubles, updated in place;  v : the block's scalar, in place
+ *   g, dtype, g_first : gradient buffer, its element type, index of the
+ *                       block's first element inside it
+ *   t >= 1 : step counter used by the bias corrections
+ */
+void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
+                    uint64_t g_first, uint64_t n, double lr, double beta1,
+                    double beta2, double eps, double lambda, uint64_t t) {
+  double bias1 = 1.0 - pow(beta1, (double)t);
+  double bias2 = 1.0 - pow(beta2, (double)t);
+
+  /* param = param - lr * lambda * param */
+  for (uint64_t i = 0; i < n; ++i) p[i] = p[i] - lr * lambda * p[i];
+
+  /* m = (1 - beta1) * g + beta1 * m */
+  for (uint64_t i = 0; i < n; ++i) {
+    double gi = amo_grad_at(g, dtype, g_first + i);
+    m[i] = (1.0 - beta1) * gi + beta1 * m[i];
+  }
+
+  /* v = (1 - beta2) * mean(g .* g) + beta2 * v : one scalar for the block */
+  double sum_sq = 0.0;
+  for (uint64_t i = 0; i < n; ++i) {
+    double gi = amo_grad_at(g, dtype, g_first + i);
+    sum_sq += gi * gi;
+  }
+  double mean_sq = sum_sq / (double)n;
+  *v = (1.0 - beta2) * mean_sq + beta2 * (*v);
+
+  /* v_hat = v / (1 - beta2^t) */
+  double v_hat = *v / bias2;
+
+  /* param = param - lr * m_hat / (sqrt(v_hat) + eps), m_hat = m / (1 - beta1^t) */
+  for (uint64_t i = 0; i < n; ++i) {
+    double m_hat = m[i] / bias1;
+    p[i] = p[i] - lr * m_hat / (sqrt(v_hat) + eps);
+  }
+}
+
+/*
+ * One step on one tensor of `numel` elements cut into numel/block_numel
+ * consecutive blocks.  v points at this tensor's first scalar (one per block).
+ * Blocks never interact, so they are handed to the host threads as they come.
+ * Returns 0, or -1 when the descriptor is not a valid uniform partition.
+ */
+int amo_step_tensor(double *p, double *m, double *v, const void *g, int dtype,
+                    uint64_t numel, uint64_t block_numel, double lr,
+                    double beta1, double beta2, double eps, double lambda,
+                    uint64_t t) {
+  if (numel == 0 || block_numel == 0 || numel % block_numel != 0 || t == 0)
+    return -1;
+  int64_t n_blocks = (int64_t)(numel / block_numel);
+#pragma omp parallel for schedule(static)
+  for (int64_t b = 0; b < n_blocks; ++b) {
+    uint64_t first = (uint64_t)b * block_numel;
+    amo_step_block(p + first, m + first, v + b, g, dtype, first, block_numel,
+                   lr, beta1, beta2, eps, lambda, t);
+  }
+  return 0;
+}
+
+/*
+ * Index of the second-moment scalar that element `elem` of tensor `tensor`
+ * uses, when the v scalars of all tensors are stored back to back in tensor
+ * order.  Written as a running count of blocks, independent of any table.
+ * Returns UINT64_MAX on a bad argument.
+ */
+uint64_t amo_block_id(const uint64_t *numel, const uint64_t *block_numel,
+                      uint32_t n_tensors, uint32_t tensor, uint64_t elem) {
+  if (tensor >= n_tensors || elem >= numel[tensor]) return UINT64_MAX;
+  uint64_t blocks_before = 0;
+  for (uint32_t k = 0; k < tensor; ++k)
+    blocks_before += numel[k] / block_numel[k];
+  return blocks_before + elem / block_numel[tensor];
+}
+
+/* Total number of v scalars of a tensor list. */
+uint64_t amo_num_blocks(const uint64_t *numel, const uint64_t *block_numel,
+                        uint32_t n_tensors) {
+  uint64_t total = 0;
+  for (uint32_t k = 0; k < n_tensors; ++k) total += numel[k] / block_numel[k];
+  return total;
+}
+
+/* Threads the tensor loop will use (for the CPU-baseline report). */
+int amo_num_threads(void) {
+#ifdef _OPENMP
+  extern int omp_get_max_threads(void);
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

@@ -1,0 +1,9 @@
+"""MI355X-native Adam-mini optimizer step (arXiv 2406.16793).
+
+``binding`` is the thin ctypes layer over the C ABI declared in
+``include/adam_mini.h``; ``partition`` turns named tensor shapes into block
+descriptors (the paper's Algorithm 3); ``workloads`` holds the seeded synthetic
+benchmark configurations.  Importing the package does not load the HIP library;
+the first use of ``binding`` does, and raises if it has not been built.
+"""
+__all__ = ["binding", "partition", "workloads"]

@@ -1,0 +1,63 @@
+"""Show that the pins bite: each plausible mistake, planted into a temporary copy
+of the oracle's C source on the CPU, must make at least one pin fail."""
+import os
+
+import pytest
+
+import oracle_pins
+
+# (label, text in oracle/adam_mini_oracle.c, replacement)
+MUTANTS = [
+    ("no weight decay", "p[i] = p[i] - lr * lambda * p[i];", "p[i] = p[i];"),
+    ("decay uses gradient scale (sign flipped)", "p[i] = p[i] - lr * lambda * p[i];", "p[i] = p[i] + lr * lambda * p[i];"),
+    ("beta1 weights swapped", "m[i] = (1.0 - beta1) * gi + beta1 * m[i];", "m[i] = beta1 * gi + (1.0 - beta1) * m[i];"),
+    ("m uses beta2", "m[i] = (1.0 - beta1) * gi + beta1 * m[i];", "m[i] = (1.0 - beta2) * gi + beta2 * m[i];"),
+    ("sum instead of mean", "double mean_sq = sum_sq / (double)n;", "double mean_sq = sum_sq;"),
+    ("mean of |g| instead of g*g", "sum_sq += gi * gi;", "sum_sq += fabs(gi);"),
+    ("square of the mean", "double mean_sq = sum_sq / (double)n;", "double mean_sq = sum_sq / (double)n; mean_sq = mean_sq * mean_sq;"),
+    ("beta2 weights swapped", "*v = (1.0 - beta2) * mean_sq + beta2 * (*v);", "*v = beta2 * mean_sq + (1.0 - beta2) * (*v);"),
+    ("v not accumulated", "*v = (1.0 - beta2) * mean_sq + beta2 * (*v);", "*v = (1.0 - beta2) * mean_sq;"),
+    ("no bias correction of m", "double m_hat = m[i] / bias1;", "double m_hat = m[i];"),
+    ("no bias correction of v", "double v_hat = *v / bias2;", "double v_hat = *v;"),
+    ("bias correction of m uses t+1", "double bias1 = 1.0 - pow(beta1, (double)t);", "double bias1 = 1.0 - pow(beta1, (double)t + 1.0);"),
+    ("bias correction of v uses t+1", "double bias2 = 1.0 - pow(beta2, (double)t);", "double bias2 = 1.0 - pow(beta2, (double)t + 1.0);"),
+    ("bias2 uses beta1", "double bias2 = 1.0 - pow(beta2, (double)t);", "double bias2 = 1.0 - pow(beta1, (double)t);"),
+    ("eps inside the root", "(sqrt(v_hat) + eps)", "sqrt(v_hat + eps)"),
+    ("eps dropped", "(sqrt(v_hat) + eps)", "(sqrt(v_hat))"),
+    ("eps added twice", "(sqrt(v_hat) + eps)", "(sqrt(v_hat) + eps + eps)"),
+    ("no square root", "(sqrt(v_hat) + eps)", "(v_hat + eps)"),
+    ("update sign", "p[i] = p[i] - lr * m_hat / (sqrt(v_hat) + eps);", "p[i] = p[i] + lr * m_hat / (sqrt(v_hat) + eps);"),
+    ("update uses g not m", "double m_hat = m[i] / bias1;", "double m_hat = amo_grad_at(g, dtype, g_first + i);"),
+    ("gradient offset ignored", "amo_step_block(p + first, m + first, v + b, g, dtype, first,", "amo_step_block(p + first, m + first, v + b, g, dtype, 0,"),
+    ("one v for the whole tensor", "amo_step_block(p + first, m + first, v + b,", "amo_step_block(p + first, m + first, v + 0 * b,"),
+    ("block id ignores earlier tensors", "return blocks_before + elem / block_numel[tensor];", "return elem / block_numel[tensor];"),
+    ("block id counts elements", "blocks_before += numel[k] / block_numel[k];", "blocks_before += numel[k];"),
+    ("block id rounds up", "return blocks_before + elem / block_numel[tensor];", "return blocks_before + (elem + block_numel[tensor] - 1) / block_numel[tensor];"),
+    ("bf16 shifted wrongly", "<< 16;", "<< 15;"),
+]
+
+
+def _failing_pins(lib):
+    failed = []
+    for pin in oracle_pins.ALL_PINS:
+        try:
+            pin(lib)
+        except AssertionError:
+            failed.append(pin.__name__)
+        except Exception:
+            failed.append(pin.__name__)
+    return failed
+
+
+@pytest.mark.parametrize("label,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(oracle, tmp_path, label, old, new):
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "adam_mini_oracle.c")).read()
+    assert src.count(old) >= 1, "mutation site not found: %r" % old
+    mutated = tmp_path / "mutant.c"
+    mutated.write_text(src.replace(old, new))
+    lib = oracle.OracleLib(oracle.compile_c(str(mutated), str(tmp_path / "libmutant.so")))
+    assert _failing_pins(lib), "no pin notices: %s" % label
+
+
+def test_unmutated_passes_all(oracle):
+    assert _failing_pins(oracle.default_lib()) == []
