@@ -157,6 +157,24 @@ int adam_mini_step(adam_mini_layout* layout, void* const* params,
                    const void* const* grads, void* const* exp_avg, float* v_dev,
                    const adam_mini_hparams* hp, void* hip_stream);
 
+/*
+ * Process-wide performance knobs, read by later adam_mini_init_layout calls (an
+ * existing layout keeps the values it was built with).  They choose which kernel
+ * variant serves a block size and how launches are shaped; they never change what
+ * is computed beyond the order of the fp32 partial sums.  Keys (value >= 0):
+ *   "subwave_max_units"  blocks of at most this many 128-bit units use 16-thread teams
+ *   "wave_max_units"     ... at most this many units: one 64-thread wavefront per block
+ *   "wide_min_units"     ... at least this many units: 1024-thread workgroups
+ *   "row_max_units"      blocks above this leave the single-pass register kernel
+ *   "lds_max_bytes"      > 0: such blocks whose gradient fits in this much LDS use the LDS-staged kernel
+ *   "large_chunk_upt"    units per thread of a chunk in the multi-workgroup path (4, 8, 16)
+ *   "ew_upt"             units per thread of a tile in the AdamW-equivalent kernel (2, 4, 8)
+ *   "grid_cap"           > 0: cap on workgroups per launch (grid-stride loop beyond it)
+ *   "reset"              restore the defaults (value ignored)
+ * Returns ADAM_MINI_INVALID_ARG for an unknown key or a negative value.
+ */
+int adam_mini_set_option(const char* key, int64_t value);
+
 /* Frees host and device resources of the layout (null is a no-op).  The caller
  * must make sure no step using the layout is still running. */
 void adam_mini_destroy_layout(adam_mini_layout* layout);

@@ -54,6 +54,8 @@ class OracleLib:
                                         dbl, dbl, dbl, dbl, dbl, u64]
         lib.amo_block_id.restype = u64
         lib.amo_block_id.argtypes = [vp, vp, ctypes.c_uint32, ctypes.c_uint32, u64]
+        lib.amo_block_ids_tensor.restype = ctypes.c_int
+        lib.amo_block_ids_tensor.argtypes = [vp, vp, ctypes.c_uint32, ctypes.c_uint32, vp]
         lib.amo_num_blocks.restype = u64
         lib.amo_num_blocks.argtypes = [vp, vp, ctypes.c_uint32]
         lib.amo_num_threads.restype = ctypes.c_int
@@ -92,6 +94,15 @@ class OracleLib:
         if r == 2 ** 64 - 1:
             raise IndexError("tensor/element out of range")
         return int(r)
+
+    def block_ids_tensor(self, numel: Sequence[int], block_numel: Sequence[int], tensor: int) -> np.ndarray:
+        """v index of every element of tensor `tensor` (uint64 array)."""
+        n = np.ascontiguousarray(numel, dtype=np.uint64)
+        b = np.ascontiguousarray(block_numel, dtype=np.uint64)
+        out = np.empty(int(n[tensor]), dtype=np.uint64)
+        if self._lib.amo_block_ids_tensor(n.ctypes.data, b.ctypes.data, len(n), tensor, out.ctypes.data) != 0:
+            raise IndexError("tensor out of range")
+        return out
 
     def num_blocks(self, numel: Sequence[int], block_numel: Sequence[int]) -> int:
         n = np.ascontiguousarray(numel, dtype=np.uint64)
@@ -149,6 +160,10 @@ def block_id(numel, block_numel, tensor, elem) -> int:
 
 def num_blocks(numel, block_numel) -> int:
     return default_lib().num_blocks(numel, block_numel)
+
+
+def block_ids_tensor(numel, block_numel, tensor) -> np.ndarray:
+    return default_lib().block_ids_tensor(numel, block_numel, tensor)
 
 
 class OracleState:

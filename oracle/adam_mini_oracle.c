@@ -133,6 +133,15 @@ uint64_t amo_block_id(const uint64_t *numel, const uint64_t *block_numel,
   return blocks_before + elem / block_numel[tensor];
 }
 
+/* amo_block_id for every element of one tensor: out[e], e = 0 .. numel[tensor]-1. */
+int amo_block_ids_tensor(const uint64_t *numel, const uint64_t *block_numel,
+                         uint32_t n_tensors, uint32_t tensor, uint64_t *out) {
+  if (tensor >= n_tensors) return -1;
+  for (uint64_t e = 0; e < numel[tensor]; ++e)
+    out[e] = amo_block_id(numel, block_numel, n_tensors, tensor, e);
+  return 0;
+}
+
 /* Total number of v scalars of a tensor list. */
 uint64_t amo_num_blocks(const uint64_t *numel, const uint64_t *block_numel,
                         uint32_t n_tensors) {

@@ -1,0 +1,488 @@
+// C ABI of the Adam-mini step library (include/adam_mini.h): argument checks,
+// device work tables, kernel dispatch.  All arithmetic is in am_kernels.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/adam_mini.h"
+#include "am_kernels.h"
+#include "am_layout.h"
+
+namespace {
+
+thread_local std::string g_hip_error;
+std::mutex g_tuning_mutex;
+AmTuning g_tuning;
+
+int hip_fail(hipError_t e, const char* what) {
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  (void)hipGetLastError();  // clear the sticky per-thread error
+  return e == hipErrorOutOfMemory ? ADAM_MINI_OUT_OF_MEMORY : ADAM_MINI_HIP_ERROR;
+}
+
+#define AM_HIP(call)                                   \
+  do {                                                 \
+    hipError_t e_ = (call);                            \
+    if (e_ != hipSuccess) return hip_fail(e_, #call);  \
+  } while (0)
+
+// RAII: make the layout's device current for the duration of a call.
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  int enter(int device) {
+    AM_HIP(hipGetDevice(&prev));
+    if (prev != device) {
+      AM_HIP(hipSetDevice(device));
+      switched = true;
+    }
+    return ADAM_MINI_OK;
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+}  // namespace
+
+struct adam_mini_layout {
+  AmHostLayout host;
+  int device = -1;
+  // device state, created by the first call that needs it
+  bool device_ready = false;
+  AmSeg* segs_dev = nullptr;       // all buckets' segments, concatenated
+  AmSeg* segs_staging = nullptr;   // pinned host copy
+  float* partials_dev = nullptr;   // LARGE: one float per chunk
+  float* scales_dev = nullptr;     // LARGE: one float per large block
+  bool tables_valid = false;       // segs_dev holds the pointers below
+  std::vector<const void*> cached_p, cached_g, cached_m;
+};
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// kernel dispatch: the variant lists must match am_layout.cpp
+// ---------------------------------------------------------------------------
+#define AM_ROW_VARIANTS(X)                                                                        \
+  X(16, 1) X(16, 2) X(16, 4) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(64, 16) X(256, 1) X(256, 2)    \
+  X(256, 3) X(256, 4) X(256, 6) X(256, 8) X(256, 12) X(256, 16) X(1024, 1) X(1024, 2) X(1024, 3) \
+  X(1024, 4)
+#define AM_LARGE_VARIANTS(X) X(256, 4) X(256, 8) X(256, 16)
+#define AM_EW_VARIANTS(X) X(256, 2) X(256, 4) X(256, 8)
+
+uint32_t grid_for(uint64_t groups, const AmTuning& t) {
+  uint64_t g = groups;
+  if (t.grid_cap > 0 && g > (uint64_t)t.grid_cap) g = (uint64_t)t.grid_cap;
+  if (g > 0x7fffffffull) g = 0x7fffffffull;
+  return (uint32_t)g;
+}
+
+template <typename G, int VEC>
+int launch_row(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, float* v, const AmScalars& sc,
+               const AmTuning& t, hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t n_segs = (uint32_t)bk.segs.size();
+#define X(L, U)                                                                                         \
+  if (var.lanes == L && var.upt == U) {                                                                 \
+    constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                                   \
+    const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                                \
+    hipLaunchKernelGGL((am_row_kernel<G, VEC, L, U>), dim3(grid), dim3(WG), 0, stream, segs, n_segs,    \
+                       n_items, v, sc);                                                                 \
+    return ADAM_MINI_OK;                                                                                \
+  }
+  AM_ROW_VARIANTS(X)
+#undef X
+  return ADAM_MINI_INVALID_ARG;
+}
+
+template <int VEC>
+int launch_row_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, uint32_t tensor, uint64_t* ids,
+                   const AmTuning& t, hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t n_segs = (uint32_t)bk.segs.size();
+#define X(L, U)                                                                                       \
+  if (var.lanes == L && var.upt == U) {                                                               \
+    constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                                 \
+    const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                              \
+    hipLaunchKernelGGL((am_row_ids<VEC, L, U>), dim3(grid), dim3(WG), 0, stream, segs, n_segs,        \
+                       n_items, tensor, ids);                                                         \
+    return ADAM_MINI_OK;                                                                              \
+  }
+  AM_ROW_VARIANTS(X)
+#undef X
+  return ADAM_MINI_INVALID_ARG;
+}
+
+template <typename G, int VEC>
+int launch_large(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, float* v, float* partials,
+                 float* scales, const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t n_segs = (uint32_t)bk.segs.size();
+  const uint32_t n_lblocks = (uint32_t)bk.n_lblocks;
+  const uint32_t grid = grid_for(bk.n_items, t);
+  const uint32_t fgrid = grid_for((bk.n_lblocks + 3) / 4, t);
+#define X(L, U)                                                                                          \
+  if (var.lanes == L && var.upt == U) {                                                                  \
+    hipLaunchKernelGGL((am_large_partial<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,   \
+                       n_items, partials);                                                               \
+    hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, segs, n_segs, n_lblocks,    \
+                       (const float*)partials, v, scales, sc);                                           \
+    hipLaunchKernelGGL((am_large_update<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,    \
+                       n_items, (const float*)scales, sc);                                               \
+    return ADAM_MINI_OK;                                                                                 \
+  }
+  AM_LARGE_VARIANTS(X)
+#undef X
+  return ADAM_MINI_INVALID_ARG;
+}
+
+template <int VEC>
+int launch_large_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, uint32_t tensor, uint64_t* ids,
+                     const AmTuning& t, hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t n_segs = (uint32_t)bk.segs.size();
+  const uint32_t grid = grid_for(bk.n_items, t);
+#define X(L, U)                                                                                      \
+  if (var.lanes == L && var.upt == U) {                                                              \
+    hipLaunchKernelGGL((am_large_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,      \
+                       n_items, tensor, ids);                                                        \
+    return ADAM_MINI_OK;                                                                             \
+  }
+  AM_LARGE_VARIANTS(X)
+#undef X
+  return ADAM_MINI_INVALID_ARG;
+}
+
+template <typename G, int VEC>
+int launch_elementwise(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, float* v,
+                       const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t n_segs = (uint32_t)bk.segs.size();
+  const uint32_t grid = grid_for(bk.n_items, t);
+#define X(L, U)                                                                                       \
+  if (var.lanes == L && var.upt == U) {                                                               \
+    hipLaunchKernelGGL((am_elementwise<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,  \
+                       n_items, v, sc);                                                               \
+    return ADAM_MINI_OK;                                                                              \
+  }
+  AM_EW_VARIANTS(X)
+#undef X
+  return ADAM_MINI_INVALID_ARG;
+}
+
+template <int VEC>
+int launch_elementwise_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, uint32_t tensor,
+                           uint64_t* ids, const AmTuning& t, hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t n_segs = (uint32_t)bk.segs.size();
+  const uint32_t grid = grid_for(bk.n_items, t);
+#define X(L, U)                                                                                          \
+  if (var.lanes == L && var.upt == U) {                                                                  \
+    hipLaunchKernelGGL((am_elementwise_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,    \
+                       n_items, tensor, ids);                                                            \
+    return ADAM_MINI_OK;                                                                                 \
+  }
+  AM_EW_VARIANTS(X)
+#undef X
+  return ADAM_MINI_INVALID_ARG;
+}
+
+// Dispatch on (gradient type, vec) -> template arguments.
+template <typename F32Fn, typename Bf16Fn, typename ScalarF32Fn, typename ScalarBf16Fn>
+int by_type(int grad_dtype, int vec, F32Fn f32, Bf16Fn bf16, ScalarF32Fn sf32, ScalarBf16Fn sbf16) {
+  if (grad_dtype == ADAM_MINI_GRAD_F32) return vec == 1 ? sf32() : f32();
+  return vec == 1 ? sbf16() : bf16();
+}
+
+int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, const AmScalars& sc,
+                       hipStream_t stream) {
+  const AmSeg* segs = L->segs_dev + bk.table_offset;
+  const AmVariant& var = bk.var;
+  const AmTuning& t = L->host.tuning;
+  const int dt = L->host.grad_dtype;
+  switch (var.family) {
+    case AM_FAM_ROW:
+      return by_type(
+          dt, var.vec, [&] { return launch_row<float, 4>(var, bk, segs, v, sc, t, stream); },
+          [&] { return launch_row<am_bf16, 8>(var, bk, segs, v, sc, t, stream); },
+          [&] { return launch_row<float, 1>(var, bk, segs, v, sc, t, stream); },
+          [&] { return launch_row<am_bf16, 1>(var, bk, segs, v, sc, t, stream); });
+    case AM_FAM_LARGE:
+      return by_type(
+          dt, var.vec,
+          [&] { return launch_large<float, 4>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); },
+          [&] { return launch_large<am_bf16, 8>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); },
+          [&] { return launch_large<float, 1>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); },
+          [&] { return launch_large<am_bf16, 1>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); });
+    case AM_FAM_ELEMENTWISE:
+      return by_type(
+          dt, var.vec, [&] { return launch_elementwise<float, 4>(var, bk, segs, v, sc, t, stream); },
+          [&] { return launch_elementwise<am_bf16, 8>(var, bk, segs, v, sc, t, stream); },
+          [&] { return launch_elementwise<float, 1>(var, bk, segs, v, sc, t, stream); },
+          [&] { return launch_elementwise<am_bf16, 1>(var, bk, segs, v, sc, t, stream); });
+    default:
+      return ADAM_MINI_INVALID_ARG;
+  }
+}
+
+int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t tensor, uint64_t* ids,
+                      hipStream_t stream) {
+  const AmSeg* segs = L->segs_dev + bk.table_offset;
+  const AmVariant& var = bk.var;
+  const AmTuning& t = L->host.tuning;
+  const int native = L->host.grad_dtype == ADAM_MINI_GRAD_BF16 ? 8 : 4;
+  const bool scalar = var.vec == 1;
+  switch (var.family) {
+    case AM_FAM_ROW:
+      if (scalar) return launch_row_ids<1>(var, bk, segs, tensor, ids, t, stream);
+      return native == 8 ? launch_row_ids<8>(var, bk, segs, tensor, ids, t, stream)
+                         : launch_row_ids<4>(var, bk, segs, tensor, ids, t, stream);
+    case AM_FAM_LARGE:
+      if (scalar) return launch_large_ids<1>(var, bk, segs, tensor, ids, t, stream);
+      return native == 8 ? launch_large_ids<8>(var, bk, segs, tensor, ids, t, stream)
+                         : launch_large_ids<4>(var, bk, segs, tensor, ids, t, stream);
+    case AM_FAM_ELEMENTWISE:
+      if (scalar) return launch_elementwise_ids<1>(var, bk, segs, tensor, ids, t, stream);
+      return native == 8 ? launch_elementwise_ids<8>(var, bk, segs, tensor, ids, t, stream)
+                         : launch_elementwise_ids<4>(var, bk, segs, tensor, ids, t, stream);
+    default:
+      return ADAM_MINI_INVALID_ARG;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// device tables
+// ---------------------------------------------------------------------------
+int ensure_device_state(adam_mini_layout* L) {
+  if (L->device_ready) return ADAM_MINI_OK;
+  const size_t seg_bytes = L->host.n_segs * sizeof(AmSeg);
+  AM_HIP(hipMalloc((void**)&L->segs_dev, seg_bytes));
+  AM_HIP(hipHostMalloc((void**)&L->segs_staging, seg_bytes, hipHostMallocDefault));
+  if (L->host.n_partials > 0) {
+    AM_HIP(hipMalloc((void**)&L->partials_dev, L->host.n_partials * sizeof(float)));
+    AM_HIP(hipMalloc((void**)&L->scales_dev, L->host.n_lblocks * sizeof(float)));
+  }
+  L->device_ready = true;
+  return ADAM_MINI_OK;
+}
+
+// Upload the work tables with the given pointer lists (null lists: pointers stay null,
+// which is enough for the id kernels).  Waits for the upload so the staging buffer can be reused.
+int upload_tables(adam_mini_layout* L, void* const* params, const void* const* grads, void* const* exp_avg,
+                  hipStream_t stream) {
+  for (const AmBucket& bk : L->host.buckets) {
+    for (size_t i = 0; i < bk.segs.size(); ++i) {
+      AmSeg s = bk.segs[i];
+      if (params) {
+        s.p = (float*)params[s.tensor];
+        s.g = grads[s.tensor];
+        s.m = (float*)exp_avg[s.tensor];
+      }
+      L->segs_staging[bk.table_offset + i] = s;
+    }
+  }
+  AM_HIP(hipMemcpyAsync(L->segs_dev, L->segs_staging, L->host.n_segs * sizeof(AmSeg), hipMemcpyHostToDevice, stream));
+  AM_HIP(hipStreamSynchronize(stream));
+  return ADAM_MINI_OK;
+}
+
+bool finite_f(float x) { return std::isfinite(x); }
+
+}  // namespace
+
+// ===========================================================================
+// exported functions
+// ===========================================================================
+extern "C" {
+
+int adam_mini_set_option(const char* key, int64_t value) {
+  if (!key) return ADAM_MINI_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_tuning_mutex);
+  const std::string k(key);
+  if (k == "reset") { g_tuning = AmTuning(); return ADAM_MINI_OK; }
+  if (value < 0) return ADAM_MINI_INVALID_ARG;
+  if (k == "subwave_max_units") g_tuning.subwave_max_units = value;
+  else if (k == "wave_max_units") g_tuning.wave_max_units = value;
+  else if (k == "wide_min_units") g_tuning.wide_min_units = value;
+  else if (k == "row_max_units") g_tuning.row_max_units = value;
+  else if (k == "lds_max_bytes") g_tuning.lds_max_bytes = value;
+  else if (k == "large_chunk_upt") g_tuning.large_chunk_upt = value;
+  else if (k == "ew_upt") g_tuning.ew_upt = value;
+  else if (k == "grid_cap") g_tuning.grid_cap = value;
+  else return ADAM_MINI_INVALID_ARG;
+  return ADAM_MINI_OK;
+}
+
+int adam_mini_init_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int grad_dtype, int device,
+                          adam_mini_layout** out) {
+  if (!out) return ADAM_MINI_INVALID_ARG;
+  *out = nullptr;
+  if (!descs || n_tensors == 0 || device < -1) return ADAM_MINI_INVALID_ARG;
+  adam_mini_layout* L = new (std::nothrow) adam_mini_layout();
+  if (!L) return ADAM_MINI_OUT_OF_MEMORY;
+  AmTuning tuning;
+  {
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
+    tuning = g_tuning;
+  }
+  int rc;
+  try {
+    rc = am_build_layout(descs, n_tensors, grad_dtype, tuning, &L->host);
+    if (rc == ADAM_MINI_OK) {
+      L->cached_p.assign(n_tensors, nullptr);
+      L->cached_g.assign(n_tensors, nullptr);
+      L->cached_m.assign(n_tensors, nullptr);
+    }
+  } catch (const std::bad_alloc&) {
+    rc = ADAM_MINI_OUT_OF_MEMORY;
+  }
+  if (rc != ADAM_MINI_OK) {
+    delete L;
+    return rc;
+  }
+  L->device = device;
+  *out = L;
+  return ADAM_MINI_OK;
+}
+
+uint64_t adam_mini_num_blocks(const adam_mini_layout* layout) { return layout ? layout->host.num_blocks : 0; }
+
+uint32_t adam_mini_num_tensors(const adam_mini_layout* layout) {
+  return layout ? (uint32_t)layout->host.tensors.size() : 0;
+}
+
+int adam_mini_export_layout(const adam_mini_layout* layout, uint64_t* v_offset, uint32_t* path_kind) {
+  if (!layout) return ADAM_MINI_INVALID_ARG;
+  const auto& ts = layout->host.tensors;
+  if (v_offset) {
+    for (size_t k = 0; k < ts.size(); ++k) v_offset[k] = ts[k].v_first;
+    v_offset[ts.size()] = layout->host.num_blocks;
+  }
+  if (path_kind) {
+    for (size_t k = 0; k < ts.size(); ++k) path_kind[k] = (uint32_t)am_path_kind(layout->host.buckets[ts[k].bucket].var);
+  }
+  return ADAM_MINI_OK;
+}
+
+int adam_mini_block_id(const adam_mini_layout* layout, uint32_t tensor, uint64_t elem, uint64_t* out) {
+  if (!layout || !out || tensor >= layout->host.tensors.size()) return ADAM_MINI_INVALID_ARG;
+  const AmTensorInfo& ti = layout->host.tensors[tensor];
+  if (elem >= ti.numel) return ADAM_MINI_INVALID_ARG;
+  *out = ti.v_first + elem / ti.block_numel;
+  return ADAM_MINI_OK;
+}
+
+int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor, uint64_t* ids_dev, void* hip_stream) {
+  if (!layout || !ids_dev || tensor >= layout->host.tensors.size()) return ADAM_MINI_INVALID_ARG;
+  if (layout->device < 0) return ADAM_MINI_NO_DEVICE;
+  if (((uintptr_t)ids_dev & 7u) != 0) return ADAM_MINI_MISALIGNED;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  DeviceGuard guard;
+  int rc = guard.enter(layout->device);
+  if (rc != ADAM_MINI_OK) return rc;
+  rc = ensure_device_state(layout);
+  if (rc != ADAM_MINI_OK) return rc;
+  if (!layout->tables_valid) {
+    // no step yet: upload the tables without data pointers (the id kernels do not use them)
+    rc = upload_tables(layout, nullptr, nullptr, nullptr, stream);
+    if (rc != ADAM_MINI_OK) return rc;
+  }
+  const AmBucket& bk = layout->host.buckets[layout->host.tensors[tensor].bucket];
+  rc = launch_bucket_ids(layout, bk, tensor, ids_dev, stream);
+  if (rc != ADAM_MINI_OK) return rc;
+  AM_HIP(hipGetLastError());
+  return ADAM_MINI_OK;
+}
+
+int adam_mini_step(adam_mini_layout* layout, void* const* params, const void* const* grads, void* const* exp_avg,
+                   float* v_dev, const adam_mini_hparams* hp, void* hip_stream) {
+  if (!layout || !params || !grads || !exp_avg || !v_dev || !hp) return ADAM_MINI_INVALID_ARG;
+  if (hp->step == 0) return ADAM_MINI_INVALID_ARG;
+  if (!finite_f(hp->lr) || !finite_f(hp->weight_decay) || !finite_f(hp->eps) || hp->eps < 0.0f)
+    return ADAM_MINI_INVALID_ARG;
+  if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
+    return ADAM_MINI_INVALID_ARG;
+  const size_t n = layout->host.tensors.size();
+  for (size_t k = 0; k < n; ++k)
+    if (!params[k] || !grads[k] || !exp_avg[k]) return ADAM_MINI_INVALID_ARG;
+  if (((uintptr_t)v_dev & 15u) != 0) return ADAM_MINI_MISALIGNED;
+  for (size_t k = 0; k < n; ++k)
+    if ((((uintptr_t)params[k] | (uintptr_t)grads[k] | (uintptr_t)exp_avg[k]) & 15u) != 0) return ADAM_MINI_MISALIGNED;
+  if (layout->device < 0) return ADAM_MINI_NO_DEVICE;
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  DeviceGuard guard;
+  int rc = guard.enter(layout->device);
+  if (rc != ADAM_MINI_OK) return rc;
+  rc = ensure_device_state(layout);
+  if (rc != ADAM_MINI_OK) return rc;
+
+  const bool same = layout->tables_valid && std::memcmp(layout->cached_p.data(), params, n * sizeof(void*)) == 0 &&
+                    std::memcmp(layout->cached_g.data(), grads, n * sizeof(void*)) == 0 &&
+                    std::memcmp(layout->cached_m.data(), exp_avg, n * sizeof(void*)) == 0;
+  if (!same) {
+    layout->tables_valid = false;
+    rc = upload_tables(layout, params, grads, exp_avg, stream);
+    if (rc != ADAM_MINI_OK) return rc;
+    std::memcpy(layout->cached_p.data(), params, n * sizeof(void*));
+    std::memcpy(layout->cached_g.data(), grads, n * sizeof(void*));
+    std::memcpy(layout->cached_m.data(), exp_avg, n * sizeof(void*));
+    layout->tables_valid = true;
+  }
+
+  // step scalars in double, rounded once
+  const double b1 = hp->beta1, b2 = hp->beta2, t = (double)hp->step;
+  const double bc1 = 1.0 - std::pow(b1, t), bc2 = 1.0 - std::pow(b2, t);
+  AmScalars sc;
+  sc.beta1 = hp->beta1;
+  sc.omb1 = (float)(1.0 - b1);
+  sc.beta2 = hp->beta2;
+  sc.omb2 = (float)(1.0 - b2);
+  sc.eps = hp->eps;
+  sc.bc2 = (float)bc2;
+  sc.step_size = (float)((double)hp->lr / bc1);
+  sc.lr_wd = (float)((double)hp->lr * (double)hp->weight_decay);
+
+  for (const AmBucket& bk : layout->host.buckets) {
+    rc = launch_bucket_step(layout, bk, v_dev, sc, stream);
+    if (rc != ADAM_MINI_OK) return rc;
+  }
+  AM_HIP(hipGetLastError());
+  return ADAM_MINI_OK;
+}
+
+void adam_mini_destroy_layout(adam_mini_layout* layout) {
+  if (!layout) return;
+  if (layout->device_ready) {
+    DeviceGuard guard;
+    if (guard.enter(layout->device) == ADAM_MINI_OK) {
+      (void)hipFree(layout->segs_dev);
+      (void)hipHostFree(layout->segs_staging);
+      if (layout->partials_dev) (void)hipFree(layout->partials_dev);
+      if (layout->scales_dev) (void)hipFree(layout->scales_dev);
+    }
+  }
+  delete layout;
+}
+
+const char* adam_mini_strerror(int status) {
+  switch (status) {
+    case ADAM_MINI_OK: return "ok";
+    case ADAM_MINI_INVALID_ARG: return "invalid argument";
+    case ADAM_MINI_MISALIGNED: return "device pointer is not 16-byte aligned";
+    case ADAM_MINI_OUT_OF_MEMORY: return "out of memory";
+    case ADAM_MINI_HIP_ERROR: return "HIP runtime error";
+    case ADAM_MINI_NO_DEVICE: return "layout was built without a device";
+    default: return "unknown status";
+  }
+}
+
+const char* adam_mini_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,209 @@
+// Device helpers for gfx950: 128-bit global access, bf16 widening, DPP wavefront
+// reductions with a fixed combination order, work-table lookup.
+#ifndef AM_DEVICE_H_
+#define AM_DEVICE_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "am_tables.h"
+
+typedef float am_f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int am_u32x4 __attribute__((ext_vector_type(4)));
+
+struct am_bf16 {
+  uint16_t bits;
+};
+
+#ifndef AM_STREAMING
+#define AM_STREAMING 1  // 1: mark the bulk loads / stores non-temporal (data is touched once per step)
+#endif
+
+// ---------------------------------------------------------------------------
+// global memory access: VEC floats at element offset `e` (e is a multiple of VEC)
+// ---------------------------------------------------------------------------
+template <int VEC>
+__device__ __forceinline__ void am_load_f32(const float* __restrict__ base, uint64_t e, float (&out)[VEC]) {
+  if constexpr (VEC == 1) {
+#if AM_STREAMING
+    out[0] = __builtin_nontemporal_load(base + e);
+#else
+    out[0] = base[e];
+#endif
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC / 4; ++j) {
+      const am_f32x4* src = reinterpret_cast<const am_f32x4*>(base + e) + j;
+#if AM_STREAMING
+      am_f32x4 t = __builtin_nontemporal_load(src);
+#else
+      am_f32x4 t = *src;
+#endif
+      out[4 * j + 0] = t.x;
+      out[4 * j + 1] = t.y;
+      out[4 * j + 2] = t.z;
+      out[4 * j + 3] = t.w;
+    }
+  }
+}
+
+template <int VEC>
+__device__ __forceinline__ void am_store_f32(float* __restrict__ base, uint64_t e, const float (&in)[VEC]) {
+  if constexpr (VEC == 1) {
+#if AM_STREAMING
+    __builtin_nontemporal_store(in[0], base + e);
+#else
+    base[e] = in[0];
+#endif
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC / 4; ++j) {
+      am_f32x4 t;
+      t.x = in[4 * j + 0];
+      t.y = in[4 * j + 1];
+      t.z = in[4 * j + 2];
+      t.w = in[4 * j + 3];
+      am_f32x4* dst = reinterpret_cast<am_f32x4*>(base + e) + j;
+#if AM_STREAMING
+      __builtin_nontemporal_store(t, dst);
+#else
+      *dst = t;
+#endif
+    }
+  }
+}
+
+__device__ __forceinline__ float am_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b); }
+
+// Gradient load, widened to fp32.  bf16 is the upper half of an fp32 word, so the
+// widening is a shift (exact).  keep_cached: the caller will read the same bytes
+// again soon (second pass of the LARGE path), so do not mark the load streaming.
+template <typename G, int VEC>
+__device__ __forceinline__ void am_load_grad(const void* __restrict__ base, uint64_t e, float (&out)[VEC]) {
+  if constexpr (sizeof(G) == 4) {
+    am_load_f32<VEC>(reinterpret_cast<const float*>(base), e, out);
+  } else if constexpr (VEC == 1) {
+    const uint16_t* src = reinterpret_cast<const uint16_t*>(base) + e;
+#if AM_STREAMING
+    uint16_t h = __builtin_nontemporal_load(src);
+#else
+    uint16_t h = *src;
+#endif
+    out[0] = am_bits_to_f32(((uint32_t)h) << 16);
+  } else {
+    static_assert(VEC == 8, "bf16 gradients are read 8 at a time (128 bits)");
+    const am_u32x4* src = reinterpret_cast<const am_u32x4*>(reinterpret_cast<const uint16_t*>(base) + e);
+#if AM_STREAMING
+    am_u32x4 t = __builtin_nontemporal_load(src);
+#else
+    am_u32x4 t = *src;
+#endif
+    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      out[2 * j + 0] = am_bits_to_f32(w[j] << 16);          // little endian: low half is the earlier element
+      out[2 * j + 1] = am_bits_to_f32(w[j] & 0xffff0000u);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// reductions.  Every lane ends with the same bits: the combination tree is fixed
+// (butterfly inside a row of 16 lanes, then rows 0..3 combined as (r0+r1)+(r2+r3)),
+// so results do not depend on scheduling.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float am_dpp(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+
+// Sum over each aligned group of 16 lanes (one DPP row).
+__device__ __forceinline__ float am_row16_sum(float x) {
+  x += am_dpp<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += am_dpp<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += am_dpp<0x141>(x);  // row_half_mirror: the other quad of the half row
+  x += am_dpp<0x140>(x);  // row_mirror: the other half row
+  return x;
+}
+
+// Sum over the 64 lanes of the wavefront.
+__device__ __forceinline__ float am_wave_sum(float x) {
+  x = am_row16_sum(x);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
+// Sum over a workgroup of WAVES wavefronts; `slots` is WAVES floats of LDS that
+// nobody else touches until the next barrier-separated reuse.  Ends with a barrier
+// passed by all threads; every thread returns the same value.
+template <int WAVES>
+__device__ __forceinline__ float am_group_sum(float x, float* slots) {
+  x = am_wave_sum(x);
+  if constexpr (WAVES == 1) {
+    return x;
+  } else {
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) slots[wave] = x;
+    __syncthreads();
+    float total = slots[0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) total += slots[w];
+    return total;
+  }
+}
+
+// Double-precision wavefront sum with a fixed butterfly (used once per large block).
+__device__ __forceinline__ double am_wave_sum_f64(double x) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+// ---------------------------------------------------------------------------
+// work-table lookup: last segment whose first key is <= key
+// ---------------------------------------------------------------------------
+struct AmByItem {
+  __device__ __forceinline__ static uint64_t key(const AmSeg& s) { return s.item_first; }
+};
+struct AmByLargeBlock {
+  __device__ __forceinline__ static uint64_t key(const AmSeg& s) { return s.lblock_first; }
+};
+
+template <typename Key>
+__device__ __forceinline__ uint32_t am_find_seg(const AmSeg* __restrict__ segs, uint32_t n_segs, uint64_t key) {
+  uint32_t lo = 0, hi = n_segs;
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (Key::key(segs[mid]) <= key) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// ---------------------------------------------------------------------------
+// the arithmetic of Algorithm 1 (Section 2.3), fp32
+// ---------------------------------------------------------------------------
+// Per-block scalars: new second moment and the step scale s = (lr/bc1) / (sqrt(v/bc2) + eps).
+__device__ __forceinline__ void am_block_scalars(float sum_sq, float n, float v_old, const AmScalars& sc,
+                                                 float* v_new, float* scale) {
+  const float mean_sq = sum_sq / n;
+  const float v = fmaf(sc.beta2, v_old, sc.omb2 * mean_sq);
+  const float v_hat = v / sc.bc2;
+  const float denom = sqrtf(v_hat) + sc.eps;
+  *v_new = v;
+  *scale = sc.step_size / denom;
+}
+
+// Elementwise part: m <- (1-beta1) g + beta1 m ; p <- p - lr*lambda_k*p ; p <- p - scale * m.
+__device__ __forceinline__ void am_update_elem(float g, float& m, float& p, float scale, float decay,
+                                               const AmScalars& sc) {
+  const float m_new = fmaf(sc.beta1, m, sc.omb1 * g);
+  float q = fmaf(-decay, p, p);
+  q = fmaf(-scale, m_new, q);
+  m = m_new;
+  p = q;
+}
+
+#endif  // AM_DEVICE_H_

@@ -1,0 +1,379 @@
+// gfx950 kernels of the Adam-mini step (Algorithm 1, Section 2.3 of the paper).
+//
+//   am_row_kernel        one block per team of LANES threads, whole block in registers:
+//                        loads g, m, p once, reduces sum(g^2), updates v, m, p.  Teams of 16
+//                        or 64 threads are packed several to a 256-thread workgroup.
+//   am_large_partial     blocks too big for one workgroup: per-chunk sum(g^2)
+//   am_large_finalize    per block: fixed-order sum of its chunk partials, v update, step scale
+//   am_large_update      per chunk: m and p update with the block's step scale
+//   am_elementwise       block_numel == 1 (AdamW-equivalent): dense v, per-element sqrt / divide
+//   am_*_ids             the same work-item -> element walks, writing v indices instead
+//
+// All bulk traffic is 128-bit per lane when the block size allows (VEC = 4 fp32
+// gradients or 8 bf16 gradients per unit); VEC = 1 is the scalar fallback for block
+// sizes that are not a whole number of units.
+#ifndef AM_KERNELS_H_
+#define AM_KERNELS_H_
+
+#include "am_device.h"
+
+// ===========================================================================
+// ROW family
+// ===========================================================================
+template <int LANES>
+struct AmRowGeom {
+  static constexpr int WG = LANES < 256 ? 256 : LANES;  // threads per workgroup
+  static constexpr int TEAMS = WG / LANES;              // blocks per workgroup pass
+  static constexpr int WAVES = LANES / 64;              // wavefronts per team (0 for 16-lane teams)
+};
+
+// What a team needs to know about its work item.
+struct AmRowItem {
+  const AmSeg* seg;
+  uint64_t block;  // block index inside the tensor
+  uint64_t elem0;  // first element of the block inside the tensor
+  bool active;
+};
+
+template <int LANES>
+__device__ __forceinline__ AmRowItem am_row_decode(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                   uint32_t n_items, uint32_t first_item) {
+  const uint32_t team = threadIdx.x / LANES;
+  uint32_t item = first_item + team;
+  AmRowItem it;
+  it.active = item < n_items;
+  if (!it.active) item = n_items - 1;  // keep the lookup in range; loads and stores are masked
+  // a team of whole wavefronts shares its item: keep the table walk on the scalar unit
+  if constexpr (LANES >= 64) item = __builtin_amdgcn_readfirstlane(item);
+  const uint32_t s = am_find_seg<AmByItem>(segs, n_segs, item);
+  it.seg = segs + s;
+  it.block = (uint64_t)item - it.seg->item_first;
+  it.elem0 = it.block * it.seg->block_numel;
+  return it;
+}
+
+// unit index handled by a team lane at unroll step k
+template <int LANES>
+__device__ __forceinline__ uint64_t am_row_unit(int k) {
+  return (uint64_t)(threadIdx.x % LANES) + (uint64_t)k * LANES;
+}
+
+template <typename G, int VEC, int LANES, int UPT>
+__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(const AmSeg* __restrict__ segs,
+                                                                      uint32_t n_segs, uint32_t n_items,
+                                                                      float* __restrict__ v, AmScalars sc) {
+  using Geom = AmRowGeom<LANES>;
+  // slot [parity][w] = sum of wavefront w; slot [parity][WAVES] = the block's old v
+  __shared__ float xch[2][(Geom::WAVES > 1 ? Geom::WAVES : 1) + 1];
+  uint32_t parity = 0;
+  for (uint32_t first = blockIdx.x * Geom::TEAMS; first < n_items; first += gridDim.x * Geom::TEAMS, parity ^= 1u) {
+    const AmRowItem it = am_row_decode<LANES>(segs, n_segs, n_items, first);
+    const AmSeg& S = *it.seg;
+    const uint64_t units = S.units_per_block;
+    const uint64_t v_idx = S.v_first + it.block;
+
+    float gv[UPT][VEC], mv[UPT][VEC], pv[UPT][VEC];
+    float v_old = 0.0f;
+    if constexpr (Geom::WAVES <= 1) {
+      // team within one wavefront: every lane reads the same scalar (one broadcast request)
+      if (it.active) v_old = v[v_idx];
+    } else {
+      // several wavefronts: only thread 0 touches v, so its later store cannot race a read
+      if (threadIdx.x == 0) v_old = v[v_idx];
+    }
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_row_unit<LANES>(k);
+      if (it.active && u < units) {
+        const uint64_t e = it.elem0 + u * VEC;
+        am_load_grad<G, VEC>(S.g, e, gv[k]);
+        am_load_f32<VEC>(S.m, e, mv[k]);
+        am_load_f32<VEC>(S.p, e, pv[k]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) gv[k][j] = 0.0f;
+      }
+    }
+    // sum of squares: per lane in unit order, then the fixed reduction tree
+    float ss = 0.0f;
+#pragma unroll
+    for (int k = 0; k < UPT; ++k)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) ss = fmaf(gv[k][j], gv[k][j], ss);
+
+    if constexpr (LANES == 16) {
+      ss = am_row16_sum(ss);
+    } else if constexpr (Geom::WAVES == 1) {
+      ss = am_wave_sum(ss);
+    } else {
+      ss = am_wave_sum(ss);
+      float* slot = xch[parity];
+      if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = ss;
+      if (threadIdx.x == 0) slot[Geom::WAVES] = v_old;
+      __syncthreads();
+      ss = slot[0];
+#pragma unroll
+      for (int w = 1; w < Geom::WAVES; ++w) ss += slot[w];
+      v_old = slot[Geom::WAVES];
+    }
+
+    float v_new, scale;
+    am_block_scalars(ss, (float)S.block_numel, v_old, sc, &v_new, &scale);
+    const float decay = sc.lr_wd * S.wd_scale;
+    if (it.active && (threadIdx.x % LANES) == 0) v[v_idx] = v_new;
+
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_row_unit<LANES>(k);
+      if (it.active && u < units) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale, decay, sc);
+        const uint64_t e = it.elem0 + u * VEC;
+        am_store_f32<VEC>(S.m, e, mv[k]);
+        am_store_f32<VEC>(S.p, e, pv[k]);
+      }
+    }
+  }
+}
+
+// Same walk, writing the v index of every element of tensor `tensor`.
+template <int VEC, int LANES, int UPT>
+__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                                   uint32_t n_items, uint32_t tensor,
+                                                                   uint64_t* __restrict__ ids) {
+  using Geom = AmRowGeom<LANES>;
+  for (uint32_t first = blockIdx.x * Geom::TEAMS; first < n_items; first += gridDim.x * Geom::TEAMS) {
+    const AmRowItem it = am_row_decode<LANES>(segs, n_segs, n_items, first);
+    const AmSeg& S = *it.seg;
+    if (!it.active || S.tensor != tensor) continue;
+    const uint64_t v_idx = S.v_first + it.block;
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_row_unit<LANES>(k);
+      if (u < S.units_per_block) {
+        const uint64_t e = it.elem0 + u * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) ids[e + j] = v_idx;
+      }
+    }
+  }
+}
+
+// ===========================================================================
+// LARGE family: a block is cut into chunks of THREADS*UPT units, one per work item
+// ===========================================================================
+struct AmChunkItem {
+  const AmSeg* seg;
+  uint64_t block;   // block index inside the tensor
+  uint64_t elem0;   // first element of the block inside the tensor
+  uint64_t unit0;   // first unit of the chunk inside the block
+  uint64_t lblock;  // index of the block among the bucket's large blocks
+};
+
+__device__ __forceinline__ AmChunkItem am_chunk_decode(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                       uint32_t item, uint32_t chunk_units) {
+  const uint32_t s = am_find_seg<AmByItem>(segs, n_segs, item);
+  AmChunkItem it;
+  it.seg = segs + s;
+  const uint64_t local = (uint64_t)item - it.seg->item_first;
+  it.block = local / it.seg->chunks_per_block;
+  const uint64_t chunk = local - it.block * it.seg->chunks_per_block;
+  it.elem0 = it.block * it.seg->block_numel;
+  it.unit0 = chunk * chunk_units;
+  it.lblock = it.seg->lblock_first + it.block;
+  return it;
+}
+
+template <int THREADS>
+__device__ __forceinline__ uint64_t am_chunk_unit(uint64_t unit0, int k) {
+  return unit0 + threadIdx.x + (uint64_t)k * THREADS;
+}
+
+template <typename G, int VEC, int THREADS, int UPT>
+__global__ __launch_bounds__(THREADS) void am_large_partial(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                            uint32_t n_items, float* __restrict__ partials) {
+  __shared__ float slots[2][THREADS / 64];
+  uint32_t parity = 0;
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x, parity ^= 1u) {
+    const AmChunkItem it = am_chunk_decode(segs, n_segs, item, THREADS * UPT);
+    const AmSeg& S = *it.seg;
+    float gv[UPT][VEC];
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
+      if (u < S.units_per_block) {
+        am_load_grad<G, VEC>(S.g, it.elem0 + u * VEC, gv[k]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) gv[k][j] = 0.0f;
+      }
+    }
+    float ss = 0.0f;
+#pragma unroll
+    for (int k = 0; k < UPT; ++k)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) ss = fmaf(gv[k][j], gv[k][j], ss);
+    ss = am_group_sum<THREADS / 64>(ss, slots[parity]);
+    if (threadIdx.x == 0) partials[item] = ss;
+  }
+}
+
+// One wavefront per large block: sums the block's chunk partials in a fixed order
+// (lane-strided, then butterfly) in double, updates v and stores the step scale.
+__global__ __launch_bounds__(256) void am_large_finalize(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                         uint32_t n_lblocks, const float* __restrict__ partials,
+                                                         float* __restrict__ v, float* __restrict__ scales,
+                                                         AmScalars sc) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t waves_per_grid = gridDim.x * 4;
+  for (uint32_t lb = blockIdx.x * 4 + (threadIdx.x >> 6); lb < n_lblocks; lb += waves_per_grid) {
+    const uint32_t s = am_find_seg<AmByLargeBlock>(segs, n_segs, lb);
+    const AmSeg& S = segs[s];
+    const uint64_t block = (uint64_t)lb - S.lblock_first;
+    const uint64_t first = S.item_first + block * S.chunks_per_block;
+    double acc = 0.0;
+    for (uint64_t c = lane; c < S.chunks_per_block; c += 64) acc += (double)partials[first + c];
+    acc = am_wave_sum_f64(acc);
+    if (lane == 0) {
+      const uint64_t v_idx = S.v_first + block;
+      float v_new, scale;
+      am_block_scalars((float)acc, (float)S.block_numel, v[v_idx], sc, &v_new, &scale);
+      v[v_idx] = v_new;
+      scales[lb] = scale;
+    }
+  }
+}
+
+template <typename G, int VEC, int THREADS, int UPT>
+__global__ __launch_bounds__(THREADS) void am_large_update(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                           uint32_t n_items, const float* __restrict__ scales,
+                                                           AmScalars sc) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmChunkItem it = am_chunk_decode(segs, n_segs, item, THREADS * UPT);
+    const AmSeg& S = *it.seg;
+    const float scale = scales[it.lblock];
+    const float decay = sc.lr_wd * S.wd_scale;
+    float gv[UPT][VEC], mv[UPT][VEC], pv[UPT][VEC];
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
+      if (u < S.units_per_block) {
+        const uint64_t e = it.elem0 + u * VEC;
+        am_load_grad<G, VEC>(S.g, e, gv[k]);
+        am_load_f32<VEC>(S.m, e, mv[k]);
+        am_load_f32<VEC>(S.p, e, pv[k]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
+      if (u < S.units_per_block) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale, decay, sc);
+        const uint64_t e = it.elem0 + u * VEC;
+        am_store_f32<VEC>(S.m, e, mv[k]);
+        am_store_f32<VEC>(S.p, e, pv[k]);
+      }
+    }
+  }
+}
+
+template <int VEC, int THREADS, int UPT>
+__global__ __launch_bounds__(THREADS) void am_large_ids(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                        uint32_t n_items, uint32_t tensor,
+                                                        uint64_t* __restrict__ ids) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmChunkItem it = am_chunk_decode(segs, n_segs, item, THREADS * UPT);
+    const AmSeg& S = *it.seg;
+    if (S.tensor != tensor) continue;
+    const uint64_t v_idx = S.v_first + it.block;
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
+      if (u < S.units_per_block) {
+        const uint64_t e = it.elem0 + u * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) ids[e + j] = v_idx;
+      }
+    }
+  }
+}
+
+// ===========================================================================
+// ELEMENTWISE family (block_numel == 1): Algorithm 1 with mean(g*g) = g*g, i.e. AdamW
+// ===========================================================================
+struct AmTileItem {
+  const AmSeg* seg;
+  uint64_t unit0;  // first unit of the tile inside the tensor
+};
+
+__device__ __forceinline__ AmTileItem am_tile_decode(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                     uint32_t item, uint32_t tile_units) {
+  const uint32_t s = am_find_seg<AmByItem>(segs, n_segs, item);
+  AmTileItem it;
+  it.seg = segs + s;
+  it.unit0 = ((uint64_t)item - it.seg->item_first) * tile_units;
+  return it;
+}
+
+template <typename G, int VEC, int THREADS, int UPT>
+__global__ __launch_bounds__(THREADS) void am_elementwise(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                          uint32_t n_items, float* __restrict__ v, AmScalars sc) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmTileItem it = am_tile_decode(segs, n_segs, item, THREADS * UPT);
+    const AmSeg& S = *it.seg;
+    float* __restrict__ vt = v + S.v_first;
+    const float decay = sc.lr_wd * S.wd_scale;
+    float gv[UPT][VEC], mv[UPT][VEC], pv[UPT][VEC], vv[UPT][VEC];
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
+      if (u < S.units_per_block) {
+        const uint64_t e = u * VEC;
+        am_load_grad<G, VEC>(S.g, e, gv[k]);
+        am_load_f32<VEC>(S.m, e, mv[k]);
+        am_load_f32<VEC>(S.p, e, pv[k]);
+        am_load_f32<VEC>(vt, e, vv[k]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
+      if (u < S.units_per_block) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          float v_new, scale;
+          am_block_scalars(gv[k][j] * gv[k][j], 1.0f, vv[k][j], sc, &v_new, &scale);
+          vv[k][j] = v_new;
+          am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale, decay, sc);
+        }
+        const uint64_t e = u * VEC;
+        am_store_f32<VEC>(S.m, e, mv[k]);
+        am_store_f32<VEC>(S.p, e, pv[k]);
+        am_store_f32<VEC>(vt, e, vv[k]);
+      }
+    }
+  }
+}
+
+template <int VEC, int THREADS, int UPT>
+__global__ __launch_bounds__(THREADS) void am_elementwise_ids(const AmSeg* __restrict__ segs, uint32_t n_segs,
+                                                              uint32_t n_items, uint32_t tensor,
+                                                              uint64_t* __restrict__ ids) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmTileItem it = am_tile_decode(segs, n_segs, item, THREADS * UPT);
+    const AmSeg& S = *it.seg;
+    if (S.tensor != tensor) continue;
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
+      if (u < S.units_per_block) {
+        const uint64_t e = u * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) ids[e + j] = S.v_first + e + j;
+      }
+    }
+  }
+}
+
+#endif  // AM_KERNELS_H_

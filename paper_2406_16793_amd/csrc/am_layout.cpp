@@ -1,0 +1,174 @@
+// Host-side layout builder (see am_layout.h).  The partition itself is the paper's
+// Algorithm 3 ("Partition for Transformers", Appendix B) already reduced by the
+// caller to one block_numel per tensor; here the v scalars are numbered and each
+// tensor is routed to the kernel variant that fits its block size.
+#include "am_layout.h"
+
+#include <cmath>
+
+namespace {
+
+struct RowChoice {
+  int lanes;
+  int upt;
+};
+
+// Row-kernel instantiations that exist (must match AM_ROW_VARIANTS in adam_mini.hip).
+const RowChoice kSubwave[] = {{16, 1}, {16, 2}, {16, 4}};
+const RowChoice kWave[] = {{64, 1}, {64, 2}, {64, 4}, {64, 8}, {64, 16}};
+const RowChoice kGroup[] = {{256, 1}, {256, 2}, {256, 3}, {256, 4}, {256, 6}, {256, 8}, {256, 12}, {256, 16}};
+const RowChoice kWide[] = {{1024, 1}, {1024, 2}, {1024, 3}, {1024, 4}};
+
+template <size_t N>
+bool pick(const RowChoice (&tab)[N], uint64_t units, RowChoice* out) {
+  for (size_t i = 0; i < N; ++i) {
+    if ((uint64_t)tab[i].lanes * (uint64_t)tab[i].upt >= units) {
+      *out = tab[i];
+      return true;
+    }
+  }
+  return false;
+}
+
+bool same_variant(const AmVariant& a, const AmVariant& b) {
+  return a.family == b.family && a.vec == b.vec && a.lanes == b.lanes && a.upt == b.upt;
+}
+
+}  // namespace
+
+int am_path_kind(const AmVariant& v) {
+  switch (v.family) {
+    case AM_FAM_ELEMENTWISE: return ADAM_MINI_PATH_ELEMENTWISE;
+    case AM_FAM_ROW: return ADAM_MINI_PATH_ROW;
+    case AM_FAM_ROW_LDS: return ADAM_MINI_PATH_ROW_LDS;
+    default: return ADAM_MINI_PATH_LARGE;
+  }
+}
+
+AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel, uint64_t v_first,
+                            const AmTuning& t) {
+  const int native = grad_dtype == ADAM_MINI_GRAD_BF16 ? 8 : 4;
+  AmVariant var{};
+  if (block_numel == 1) {
+    // AdamW-equivalent: dense v.  128-bit access needs whole units and a 16-byte aligned v slice.
+    var.family = AM_FAM_ELEMENTWISE;
+    var.vec = (numel % (uint64_t)native == 0 && v_first % 4 == 0) ? native : 1;
+    var.lanes = 256;
+    var.upt = (t.ew_upt == 2 || t.ew_upt == 8) ? (int)t.ew_upt : 4;
+    return var;
+  }
+  // Every block starts on a 16-byte boundary iff block_numel is a whole number of units.
+  var.vec = (block_numel % (uint64_t)native == 0) ? native : 1;
+  const uint64_t units = block_numel / (uint64_t)var.vec;
+  RowChoice c{};
+  bool found = false;
+  if (units <= (uint64_t)t.row_max_units) {
+    if (units <= (uint64_t)t.subwave_max_units) found = pick(kSubwave, units, &c);
+    if (!found && units <= (uint64_t)t.wave_max_units) found = pick(kWave, units, &c);
+    // 1024 threads leave 128 registers per lane: 4 units of 8 elements do not fit
+    const bool wide_ok = !(var.vec == 8 && units > 3 * 1024);
+    if (!found && wide_ok && units >= (uint64_t)t.wide_min_units) found = pick(kWide, units, &c);
+    if (!found) found = pick(kGroup, units, &c);
+    if (!found && wide_ok) found = pick(kWide, units, &c);
+  }
+  if (found) {
+    var.family = AM_FAM_ROW;
+    var.lanes = c.lanes;
+    var.upt = c.upt;
+    return var;
+  }
+  const uint64_t g_bytes = block_numel * (grad_dtype == ADAM_MINI_GRAD_BF16 ? 2u : 4u);
+  if (t.lds_max_bytes > 0 && g_bytes <= (uint64_t)t.lds_max_bytes && var.vec > 1) {
+    var.family = AM_FAM_ROW_LDS;
+    var.lanes = 1024;
+    var.upt = 1;
+    return var;
+  }
+  var.family = AM_FAM_LARGE;
+  var.lanes = 256;
+  var.upt = (t.large_chunk_upt == 4 || t.large_chunk_upt == 16) ? (int)t.large_chunk_upt : 8;
+  return var;
+}
+
+int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int grad_dtype,
+                    const AmTuning& tuning, AmHostLayout* out) {
+  if (!descs || !out || n_tensors == 0) return ADAM_MINI_INVALID_ARG;
+  if (grad_dtype != ADAM_MINI_GRAD_F32 && grad_dtype != ADAM_MINI_GRAD_BF16) return ADAM_MINI_INVALID_ARG;
+  out->grad_dtype = grad_dtype;
+  out->tuning = tuning;
+  out->tensors.clear();
+  out->buckets.clear();
+  uint64_t v_next = 0;
+  for (uint32_t k = 0; k < n_tensors; ++k) {
+    const adam_mini_tensor_desc& d = descs[k];
+    if (d.numel == 0 || d.block_numel == 0 || d.numel % d.block_numel != 0) return ADAM_MINI_INVALID_ARG;
+    if (d.flags != 0) return ADAM_MINI_INVALID_ARG;
+    if (!std::isfinite(d.wd_scale) || d.wd_scale < 0.0f) return ADAM_MINI_INVALID_ARG;
+    if (d.numel >= (1ull << 48)) return ADAM_MINI_INVALID_ARG;  // keeps every product below in 64 bits
+    AmTensorInfo ti{};
+    ti.numel = d.numel;
+    ti.block_numel = d.block_numel;
+    ti.wd_scale = d.wd_scale;
+    ti.n_blocks = d.numel / d.block_numel;
+    ti.v_first = v_next;
+    v_next += ti.n_blocks;
+
+    const AmVariant var = am_choose_variant(grad_dtype, d.numel, d.block_numel, ti.v_first, tuning);
+    int b = -1;
+    for (size_t i = 0; i < out->buckets.size(); ++i)
+      if (same_variant(out->buckets[i].var, var)) b = (int)i;
+    if (b < 0) {
+      AmBucket nb;
+      nb.var = var;
+      out->buckets.push_back(nb);
+      b = (int)out->buckets.size() - 1;
+    }
+    AmBucket& bk = out->buckets[b];
+
+    AmSeg s{};
+    s.p = nullptr;
+    s.g = nullptr;
+    s.m = nullptr;
+    s.v_first = ti.v_first;
+    s.item_first = bk.n_items;
+    s.block_numel = d.block_numel;
+    s.chunks_per_block = 1;
+    s.lblock_first = bk.n_lblocks;
+    s.tensor = k;
+    s.wd_scale = d.wd_scale;
+    uint64_t items = 0;
+    if (var.family == AM_FAM_ELEMENTWISE) {
+      s.block_numel = d.numel;
+      s.units_per_block = (d.numel + (uint64_t)var.vec - 1) / (uint64_t)var.vec;
+      items = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
+    } else if (var.family == AM_FAM_ROW || var.family == AM_FAM_ROW_LDS) {
+      s.units_per_block = d.block_numel / (uint64_t)var.vec;
+      items = ti.n_blocks;
+    } else {
+      s.units_per_block = d.block_numel / (uint64_t)var.vec;
+      s.chunks_per_block = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
+      items = ti.n_blocks * s.chunks_per_block;
+      bk.n_lblocks += ti.n_blocks;
+    }
+    bk.n_items += items;
+    // a launch indexes work items with 32 bits
+    if (bk.n_items >= (1ull << 31) || bk.n_lblocks >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
+    ti.bucket = b;
+    ti.seg = (int)bk.segs.size();
+    bk.segs.push_back(s);
+    out->tensors.push_back(ti);
+  }
+  out->num_blocks = v_next;
+  out->n_partials = 0;
+  out->n_lblocks = 0;
+  out->n_segs = 0;
+  for (AmBucket& bk : out->buckets) {
+    bk.table_offset = out->n_segs;
+    out->n_segs += bk.segs.size();
+    if (bk.var.family == AM_FAM_LARGE) {
+      if (bk.n_items > out->n_partials) out->n_partials = bk.n_items;
+      if (bk.n_lblocks > out->n_lblocks) out->n_lblocks = bk.n_lblocks;
+    }
+  }
+  return ADAM_MINI_OK;
+}

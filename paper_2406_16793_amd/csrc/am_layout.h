@@ -1,0 +1,72 @@
+// Host-side layout builder: descriptors -> v offsets, kernel variant per tensor,
+// launch buckets and their work tables.  Pure C++ (no HIP), so it can be exercised
+// on a machine without a GPU.
+#ifndef AM_LAYOUT_H_
+#define AM_LAYOUT_H_
+
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/adam_mini.h"
+#include "am_tables.h"
+
+struct AmTensorInfo {
+  uint64_t numel;
+  uint64_t block_numel;
+  float wd_scale;
+  uint64_t v_first;   // exclusive prefix sum of numel / block_numel
+  uint64_t n_blocks;
+  int bucket;         // index into AmHostLayout::buckets
+  int seg;            // index into that bucket's segs
+};
+
+struct AmBucket {
+  AmVariant var;
+  std::vector<AmSeg> segs;  // pointers left null here; filled at step time
+  uint64_t n_items = 0;     // total work items (ROW: blocks, LARGE: chunks, ELEMENTWISE: tiles)
+  uint64_t n_lblocks = 0;   // LARGE: total blocks (length of the scale scratch)
+  uint64_t table_offset = 0;  // index of segs[0] in the concatenated device table
+};
+
+// Knobs of the variant choice (process-wide defaults; copied into a layout when it is built).
+struct AmTuning {
+  int64_t subwave_max_units = 64;   // blocks of <= this many units: 16-thread teams
+  int64_t wave_max_units = 256;     // blocks of <= this many units: one 64-thread wavefront each
+  int64_t wide_min_units = 1 << 30; // blocks of >= this many units: 1024-thread workgroups
+  int64_t row_max_units = 4096;     // blocks above this go to the multi-workgroup (LARGE) path
+  int64_t lds_max_bytes = 0;        // > 0: blocks above row_max_units whose gradient fits in this
+                                    //      many bytes of LDS use the LDS-staged single-pass kernel
+  int64_t large_chunk_upt = 8;      // LARGE: units per thread of a 256-thread chunk (4, 8 or 16)
+  int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (2, 4 or 8)
+  int64_t grid_cap = 0;             // > 0: at most this many workgroups per launch (grid-stride beyond)
+};
+
+struct AmHostLayout {
+  int grad_dtype = 0;
+  AmTuning tuning;
+  std::vector<AmTensorInfo> tensors;
+  std::vector<AmBucket> buckets;
+  uint64_t num_blocks = 0;    // length of v
+  uint64_t n_partials = 0;    // max over LARGE buckets of n_items   (scratch floats)
+  uint64_t n_lblocks = 0;     // max over LARGE buckets of n_lblocks (scratch floats)
+  uint64_t n_segs = 0;        // total segments over all buckets
+};
+
+// Returns ADAM_MINI_OK or ADAM_MINI_INVALID_ARG.
+int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int grad_dtype,
+                    const AmTuning& tuning, AmHostLayout* out);
+
+// Kernel variant that serves a tensor.
+AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel, uint64_t v_first,
+                            const AmTuning& tuning);
+
+// Units a team of the row kernel variant (lanes, upt) can hold.
+inline uint64_t am_row_capacity(const AmVariant& v) { return (uint64_t)v.lanes * (uint64_t)v.upt; }
+
+// Work items per workgroup-sized chunk / tile for the LARGE and ELEMENTWISE families.
+inline uint64_t am_tile_units(const AmVariant& v) { return (uint64_t)v.lanes * (uint64_t)v.upt; }
+
+int am_path_kind(const AmVariant& v);
+
+#endif  // AM_LAYOUT_H_

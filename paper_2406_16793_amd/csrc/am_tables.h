@@ -1,0 +1,55 @@
+// Work tables shared by the host layout builder and the gfx950 kernels.
+//
+// A step is a handful of launches; each launch ("bucket") serves every tensor that
+// was assigned the same kernel variant.  A bucket's work items are numbered
+// 0 .. n_items-1 across all its tensors; AmSeg records where one tensor's items
+// start, so a workgroup finds its tensor with a binary search over item_first.
+#ifndef AM_TABLES_H_
+#define AM_TABLES_H_
+
+#include <stdint.h>
+
+// Kernel families.
+enum AmFamily : int {
+  AM_FAM_ELEMENTWISE = 0,  // block_numel == 1; item = tile of units of one tensor
+  AM_FAM_ROW = 1,          // item = one block, held in the registers of a team of LANES threads
+  AM_FAM_LARGE = 2,        // item = one chunk of a block; partial sums + finalize + update
+  AM_FAM_ROW_LDS = 3       // item = one block, gradient staged in the workgroup's LDS
+};
+
+// One tensor inside one bucket.  Device pointers are filled in at step time.
+struct AmSeg {
+  float* p;               // params (fp32)
+  const void* g;          // grads (fp32 or bf16)
+  float* m;               // first moment (fp32)
+  uint64_t v_first;       // index of the tensor's first scalar in v
+  uint64_t item_first;    // number of work items of the bucket before this tensor
+  uint64_t block_numel;   // elements per block (ELEMENTWISE: numel of the tensor)
+  uint64_t units_per_block;  // block_numel / VEC (ELEMENTWISE: ceil(numel / VEC))
+  uint64_t chunks_per_block; // LARGE: work items per block; otherwise 1
+  uint64_t lblock_first;  // LARGE: number of large blocks of the bucket before this tensor
+  uint32_t tensor;        // index in the caller's tensor list
+  float wd_scale;         // lambda_k = weight_decay * wd_scale
+};
+
+// Per-step scalars, computed on the host in double and rounded once to fp32.
+struct AmScalars {
+  float beta1;      // beta1
+  float omb1;       // 1 - beta1
+  float beta2;      // beta2
+  float omb2;       // 1 - beta2
+  float eps;        // eps
+  float bc2;        // 1 - beta2^t
+  float step_size;  // lr / (1 - beta1^t)
+  float lr_wd;      // lr * weight_decay
+};
+
+// Variant of a kernel family: how a block (or tile) is spread over threads.
+struct AmVariant {
+  int family;  // AmFamily
+  int vec;     // elements per unit: 1 (scalar fallback), 4 (fp32 grads) or 8 (bf16 grads)
+  int lanes;   // threads cooperating on one item
+  int upt;     // units per thread (compile-time unroll)
+};
+
+#endif  // AM_TABLES_H_

@@ -1,0 +1,128 @@
+"""Shared helpers of the GPU parity tests: run the HIP library and the CPU oracle
+on the same seeded inputs and compare element by element."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle as orc
+from paper_2406_16793_amd import binding as B
+from paper_2406_16793_amd import workloads
+from paper_2406_16793_amd.partition import TensorSpec
+
+
+def bf16_bits(t):
+    """torch.bfloat16 tensor (any device) -> numpy uint16 bit patterns on the host."""
+    import torch
+    return t.detach().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def grad_to_host(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return bf16_bits(t)
+    return t.detach().cpu().numpy()
+
+
+def assert_state_close(name, got, want, rtol, is_v=False):
+    """Elementwise bound  |got - want| <= rtol*|want| + rtol*rms(want)  for p and m (rms over
+    the tensor's finite entries), and  <= rtol*|want| + 1e-30  for v.  Non-finite entries
+    must coincide.  Returns the normwise relative error over the finite entries."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, name
+    ok = np.isfinite(want)
+    assert np.array_equal(np.isfinite(got), ok), "%s: non-finite pattern differs" % name
+    w = np.where(ok, want, 0.0)
+    d = np.where(ok, got - want, 0.0)
+    if is_v:
+        tol = rtol * np.abs(w) + 1e-30
+    else:
+        rms = float(np.sqrt(np.sum(np.square(w)) / max(1, int(ok.sum()))))
+        tol = rtol * np.abs(w) + rtol * rms
+    err = np.abs(d)
+    bad = err > tol
+    if bad.any():
+        i = int(np.argmax(err - tol))
+        raise AssertionError("%s: %d of %d elements off; worst idx %d got %.9g want %.9g err %.3g tol %.3g"
+                             % (name, int(bad.sum()), got.size, i, got[i], want[i], err[i], tol[i]))
+    denom = float(np.linalg.norm(w))
+    return float(np.linalg.norm(d) / denom) if denom > 0 else 0.0
+
+
+class GpuRun:
+    """Device state of one tensor list plus the HIP optimizer bound to it."""
+
+    def __init__(self, specs, grad_dtype, device=0):
+        import torch
+        self.torch = torch
+        self.specs = list(specs)
+        self.grad_dtype = grad_dtype
+        self.dev = torch.device("cuda:%d" % device)
+        self.opt = B.AdamMini(self.specs, grad_dtype, device)
+        gdt = torch.bfloat16 if grad_dtype == "bf16" else torch.float32
+        self.p = [torch.empty(s.numel, dtype=torch.float32, device=self.dev) for s in self.specs]
+        self.m = [torch.zeros(s.numel, dtype=torch.float32, device=self.dev) for s in self.specs]
+        self.g = [torch.zeros(s.numel, dtype=gdt, device=self.dev) for s in self.specs]
+        self.v = torch.zeros(self.opt.num_blocks, dtype=torch.float32, device=self.dev)
+        self.opt.bind(self.p, self.g, self.m, self.v)
+
+    def close(self):
+        self.opt.close()
+
+
+def make_specs(blocks):
+    """blocks: list of (n_blocks, block_numel[, wd_scale]) -> TensorSpec list."""
+    out = []
+    for i, b in enumerate(blocks):
+        wd = b[2] if len(b) > 2 else 1.0
+        out.append(TensorSpec("t%d" % i, (b[0], b[1]), b[1], wd))
+    return out
+
+
+def run_both(wl: workloads.Workload, steps=None, hp=None, mutate_grad=None, check_every_step=False,
+             gen_device="cpu"):
+    """Steps the HIP library and the oracle over the whole workload `wl` with the same
+    inputs and compares p, m and v after the last step (or after every step).
+    Returns (GpuRun, OracleState, worst normwise relative error)."""
+    import torch
+    steps = wl.steps if steps is None else steps
+    run = GpuRun(wl.specs, wl.grad_dtype)
+    p0 = []
+    for k, s in enumerate(wl.specs):
+        x = workloads.init_param(s, wl.seed, k, device=gen_device)
+        run.p[k].copy_(x)
+        p0.append(x.cpu().numpy())
+    st = orc.OracleState([s.numel for s in wl.specs], [s.block_numel for s in wl.specs],
+                         [s.wd_scale for s in wl.specs], p0)
+    hp = hp or dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
+    ohp = orc.Hyper.from_f32(**hp)
+    worst = 0.0
+    gdt = workloads.torch_grad_dtype(wl)
+    for t in range(1, steps + 1):
+        host_g = []
+        for k, s in enumerate(wl.specs):
+            g = torch.empty(s.numel, dtype=gdt, device=gen_device)
+            workloads.fill_grad(g, s, wl, k, t)
+            if mutate_grad is not None:
+                mutate_grad(k, t, g)
+            run.g[k].copy_(g)
+            host_g.append(grad_to_host(g))
+        run.opt.step(step=t, **hp)
+        st.step(host_g, ohp)
+        if check_every_step or t == steps:
+            torch.cuda.synchronize()
+            worst = max(worst, compare(run, st, wl.rtol, "step %d" % t))
+    return run, st, worst
+
+
+def compare(run: GpuRun, st: orc.OracleState, rtol: float, label="") -> float:
+    worst = 0.0
+    v = run.v.cpu().numpy()
+    off = 0
+    for k, s in enumerate(run.specs):
+        nb = s.numel // s.block_numel
+        worst = max(worst, assert_state_close("%s param[%d] %s" % (label, k, s.name), run.p[k].cpu().numpy(), st.p[k], rtol))
+        worst = max(worst, assert_state_close("%s m[%d] %s" % (label, k, s.name), run.m[k].cpu().numpy(), st.m[k], rtol))
+        worst = max(worst, assert_state_close("%s v[%d] %s" % (label, k, s.name), v[off:off + nb], st.v[k], rtol, is_v=True))
+        off += nb
+    return worst
