@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the Adam-mini optimizer step on one MI355X.
+
+A "step" is one pass of the whole hot path -- every launch of adam_mini_step over
+the complete tensor list of the workload -- with parameters, first moments,
+gradients and v already resident in HBM.  Prints ONE JSON line:
+  value       whole-job step throughput in Gparams/s (parameters updated per second / 1e9)
+  roofline    dominant kernel: algorithmic bytes per launch / its mean duration measured with
+              HIP events on the step's stream during the timed steps, against 8 TB/s
+  cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama2_7b",
+                    help="tiny | gpt2_small | llama2_7b | llama3_8b | llama2_13b")
+    ap.add_argument("--adamw", action="store_true", help="AdamW-equivalent mode: every block of size 1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
+                    help="adam_mini_set_option before the layout is built (repeatable)")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("#") or "=" not in line:
+            continue
+        kv = dict(tok.split("=", 1) for tok in line.split("\t") if "=" in tok)
+        if kv.get("kernel") == kernel and "hbm_bytes_per_launch" in kv:
+            return float(kv["hbm_bytes_per_launch"])
+    return None
+
+
+def cpu_baseline(wl, run, hp, target_seconds):
+    """Time the oracle (as it stands) on this machine's host cores over a bounded sample: the tensors
+    of the first transformer layer, whole, stepped until about target_seconds have been spent."""
+    import numpy as np
+    import oracle as orc
+    from paper_2406_16793_amd.device_state import grad_to_host
+    idx = [k for k, s in enumerate(wl.specs) if ".0." in s.name] or list(range(min(4, len(wl.specs))))
+    specs = [wl.specs[k] for k in idx]
+    st = orc.OracleState([s.numel for s in specs], [s.block_numel for s in specs],
+                         [s.wd_scale for s in specs], [run.p[k].cpu().numpy() for k in idx])
+    grads = [grad_to_host(run.g[k]) for k in idx]
+    ohp = orc.Hyper.from_f32(**hp)
+    n = sum(s.numel for s in specs)
+    spent, steps = 0.0, 0
+    while True:
+        t0 = time.perf_counter()
+        st.step(grads, ohp)
+        dt = time.perf_counter() - t0
+        spent += dt
+        steps += 1
+        if spent + dt > target_seconds or steps >= 2000:
+            break
+    return {"value": n * steps / spent / 1e9, "unit": "Gparams/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "%d tensors of layer 0 (%d params, %d blocks), %d oracle steps, %.1f s"
+                      % (len(specs), n, sum(s.n_blocks for s in specs), steps, spent)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+                         "--gpus %d is not supported, use --gpus 1\n" % args.gpus)
+        sys.exit(2)
+    import torch
+    from paper_2406_16793_amd import binding as B
+    from paper_2406_16793_amd import partition, workloads
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2406_16793_amd import build as _build
+        _build.build()
+    from paper_2406_16793_amd.device_state import DeviceState
+
+    for kv in args.option:
+        k, v = kv.split("=", 1)
+        B.adam_mini_set_option(k, int(v))
+    wl = workloads.get(args.workload)
+    if args.adamw:
+        wl.specs = partition.as_adamw(wl.specs)
+    hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
+
+    torch.cuda.set_device(0)
+    run = DeviceState(wl.specs, wl.grad_dtype)
+    for k, s in enumerate(wl.specs):
+        run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
+        workloads.fill_grad(run.g[k], s, wl, k, 1, row_chunk=8192)
+    torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=run.dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        src.fill_(1.0)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    stream = torch.cuda.current_stream().cuda_stream
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        run.opt.step(step=t, stream=stream, **hp)
+    torch.cuda.synchronize()
+    B.adam_mini_profile_enable(run.opt.layout, args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        t += 1
+        run.opt.step(step=t, stream=stream, **hp)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    buckets = B.adam_mini_profile_read(run.opt.layout)
+    B.adam_mini_profile_enable(run.opt.layout, 0)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    n_params = sum(s.numel for s in wl.specs)
+    n_blocks = run.opt.num_blocks
+    gb = 2 if wl.grad_dtype == "bf16" else 4
+    per_param = gb + 16 + (8 if args.adamw else 0)
+
+    def algo_bytes(b):
+        return b["numel"] * per_param + (0 if args.adamw else 8 * b["n_blocks"])
+
+    dom = max(buckets, key=lambda b: b["total_ms"])
+    dom_ms = dom["total_ms"] / max(1, dom["timed_launches"])
+    achieved = algo_bytes(dom) / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic_from_profiles(args.workload + ("_adamw" if args.adamw else ""), dom["kernel"]),
+                "kernel": dom["kernel"], "kernel_ms": round(dom_ms, 4),
+                "algorithmic_bytes_per_launch": algo_bytes(dom)}
+    whole_gbs = (n_params * per_param + (0 if args.adamw else 8 * n_blocks)) / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "optimizer step Gparams/s + achieved HBM GB/s (% of peak), Llama-2-7B shape",
+        "value": round(n_params / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "Gparams/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name + ("_adamw" if args.adamw else ""), "params": n_params, "blocks": n_blocks,
+                   "tensors": len(wl.specs), "grad_dtype": wl.grad_dtype, "state_dtype": "f32",
+                   "launches_per_step": sum(b["n_kernels"] for b in buckets)},
+        "whole_step": {"algorithmic_GBps": round(whole_gbs, 1), "frac_of_peak": round(whole_gbs / HBM_PEAK_GBS, 4),
+                       "bytes_per_param": per_param},
+        "roofline": roofline,
+        "buckets": [{"kernel": b["kernel"], "params": b["numel"], "blocks": b["n_blocks"],
+                     "ms": round(b["total_ms"] / max(1, b["timed_launches"]), 4),
+                     "GBps": round(algo_bytes(b) / (b["total_ms"] / max(1, b["timed_launches"]) * 1e-3) / 1e9, 1)
+                     if b["total_ms"] > 0 else None} for b in buckets],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, run, hp, args.cpu_seconds)
+    else:
+        out["cpu_baseline"] = None
+    run.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

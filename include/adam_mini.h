@@ -158,6 +158,43 @@ int adam_mini_step(adam_mini_layout* layout, void* const* params,
                    const adam_mini_hparams* hp, void* hip_stream);
 
 /*
+ * Launch structure and timing.  A step is a short sequence of launches ("buckets"):
+ * all tensors served by the same kernel variant share one launch (three for the
+ * multi-workgroup path: partial sums, finalize, update).
+ */
+typedef struct adam_mini_bucket_info {
+  int32_t family;          /* ADAM_MINI_PATH_* */
+  int32_t vec;             /* elements per 128-bit unit (4 or 8), 1 = scalar fallback */
+  int32_t lanes;           /* threads cooperating on one work item */
+  int32_t upt;             /* units per thread */
+  uint32_t n_tensors;      /* tensors served by this bucket */
+  uint32_t n_kernels;      /* kernel launches per step (1, or 3 for ADAM_MINI_PATH_LARGE) */
+  uint64_t n_items;        /* work items per launch */
+  uint64_t numel;          /* parameters updated per launch */
+  uint64_t n_blocks;       /* v scalars updated per launch */
+  uint64_t timed_launches; /* steps whose launch of this bucket was timed since the last read */
+  double total_ms;         /* sum of those durations (HIP events on the step's stream) */
+  char kernel[96];         /* name of the (main) kernel, as a profiler prints it */
+} adam_mini_bucket_info;
+
+/* Number of buckets of the layout (0 if null). */
+uint32_t adam_mini_num_buckets(const adam_mini_layout* layout);
+
+/*
+ * Turn per-bucket timing on (max_steps > 0: HIP events are created now, and the next
+ * max_steps calls of adam_mini_step record one event pair around each bucket on the
+ * step's stream) or off (max_steps == 0: events destroyed).  Needs a device layout.
+ */
+int adam_mini_profile_enable(adam_mini_layout* layout, uint32_t max_steps);
+
+/*
+ * Fill out[0 .. min(capacity, num_buckets)) .  If timing is on, first waits for the
+ * recorded events, adds their elapsed times into total_ms / timed_launches and rearms
+ * the event pool.  Works on a host-only layout too (timing fields are then zero).
+ */
+int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out, uint32_t capacity);
+
+/*
  * Process-wide performance knobs, read by later adam_mini_init_layout calls (an
  * existing layout keeps the values it was built with).  They choose which kernel
  * variant serves a block size and how launches are shaped; they never change what

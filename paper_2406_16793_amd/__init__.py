@@ -6,4 +6,4 @@ descriptors (the paper's Algorithm 3); ``workloads`` holds the seeded synthetic
 benchmark configurations.  Importing the package does not load the HIP library;
 the first use of ``binding`` does, and raises if it has not been built.
 """
-__all__ = ["binding", "partition", "workloads"]
+__all__ = ["binding", "device_state", "partition", "workloads"]

@@ -29,6 +29,14 @@ class HParams(ctypes.Structure):
                 ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("step", ctypes.c_uint64)]
 
 
+class BucketInfo(ctypes.Structure):
+    _fields_ = [("family", ctypes.c_int32), ("vec", ctypes.c_int32), ("lanes", ctypes.c_int32),
+                ("upt", ctypes.c_int32), ("n_tensors", ctypes.c_uint32), ("n_kernels", ctypes.c_uint32),
+                ("n_items", ctypes.c_uint64), ("numel", ctypes.c_uint64), ("n_blocks", ctypes.c_uint64),
+                ("timed_launches", ctypes.c_uint64), ("total_ms", ctypes.c_double),
+                ("kernel", ctypes.c_char * 96)]
+
+
 class AdamMiniError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -42,7 +50,8 @@ _lib = None
 
 EXPORTS = ["adam_mini_init_layout", "adam_mini_num_blocks", "adam_mini_num_tensors",
            "adam_mini_export_layout", "adam_mini_block_id", "adam_mini_write_block_ids",
-           "adam_mini_step", "adam_mini_set_option", "adam_mini_destroy_layout",
+           "adam_mini_step", "adam_mini_set_option", "adam_mini_num_buckets",
+           "adam_mini_profile_enable", "adam_mini_profile_read", "adam_mini_destroy_layout",
            "adam_mini_strerror", "adam_mini_last_hip_error"]
 
 
@@ -55,6 +64,13 @@ def load(path: Optional[str] = None):
     if not os.path.exists(p):
         raise FileNotFoundError(
             "%s is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')" % p)
+    # PyTorch ships its own copy of the HIP runtime (same soname).  Device pointers and
+    # streams come from torch, so the library must bind to THAT runtime: load torch first,
+    # otherwise the process ends up with two runtimes that do not see each other's memory.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(p)
     vp, u32, u64, i32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int
     lib.adam_mini_init_layout.restype = i32
@@ -72,6 +88,12 @@ def load(path: Optional[str] = None):
     lib.adam_mini_step.restype = i32
     lib.adam_mini_step.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
                                    ctypes.POINTER(HParams), vp]
+    lib.adam_mini_num_buckets.restype = u32
+    lib.adam_mini_num_buckets.argtypes = [vp]
+    lib.adam_mini_profile_enable.restype = i32
+    lib.adam_mini_profile_enable.argtypes = [vp, u32]
+    lib.adam_mini_profile_read.restype = i32
+    lib.adam_mini_profile_read.argtypes = [vp, ctypes.POINTER(BucketInfo), u32]
     lib.adam_mini_set_option.restype = i32
     lib.adam_mini_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     lib.adam_mini_destroy_layout.restype = None
@@ -146,6 +168,22 @@ def adam_mini_step(layout: int, params, grads, exp_avg, v_dev_ptr: int, hp: HPar
     """params / grads / exp_avg: ctypes arrays of c_void_p holding device pointers."""
     _check(load().adam_mini_step(layout, params, grads, exp_avg, ctypes.c_void_p(v_dev_ptr),
                                  ctypes.byref(hp), ctypes.c_void_p(stream)), "adam_mini_step")
+
+
+def adam_mini_num_buckets(layout: int) -> int:
+    return int(load().adam_mini_num_buckets(layout))
+
+
+def adam_mini_profile_enable(layout: int, max_steps: int) -> None:
+    _check(load().adam_mini_profile_enable(layout, int(max_steps)), "adam_mini_profile_enable")
+
+
+def adam_mini_profile_read(layout: int) -> List[dict]:
+    n = adam_mini_num_buckets(layout)
+    arr = (BucketInfo * max(1, n))()
+    _check(load().adam_mini_profile_read(layout, arr, n), "adam_mini_profile_read")
+    return [{f: (getattr(arr[i], f).decode() if f == "kernel" else getattr(arr[i], f))
+             for f, _ in BucketInfo._fields_} for i in range(n)]
 
 
 def adam_mini_destroy_layout(layout: int) -> None:

@@ -62,6 +62,12 @@ struct adam_mini_layout {
   float* scales_dev = nullptr;     // LARGE: one float per large block
   bool tables_valid = false;       // segs_dev holds the pointers below
   std::vector<const void*> cached_p, cached_g, cached_m;
+  // optional per-bucket timing: events[(step * n_buckets + bucket) * 2 + {0,1}]
+  std::vector<hipEvent_t> events;
+  uint32_t profile_capacity = 0;   // steps the pool can hold
+  uint32_t profile_used = 0;       // steps recorded since the last read
+  std::vector<double> bucket_ms;
+  std::vector<uint64_t> bucket_launches;
 };
 
 namespace {
@@ -449,11 +455,102 @@ int adam_mini_step(adam_mini_layout* layout, void* const* params, const void* co
   sc.step_size = (float)((double)hp->lr / bc1);
   sc.lr_wd = (float)((double)hp->lr * (double)hp->weight_decay);
 
-  for (const AmBucket& bk : layout->host.buckets) {
-    rc = launch_bucket_step(layout, bk, v_dev, sc, stream);
+  const size_t nb = layout->host.buckets.size();
+  const bool timed = layout->profile_used < layout->profile_capacity;
+  for (size_t b = 0; b < nb; ++b) {
+    hipEvent_t* ev = timed ? &layout->events[((size_t)layout->profile_used * nb + b) * 2] : nullptr;
+    if (ev) AM_HIP(hipEventRecord(ev[0], stream));
+    rc = launch_bucket_step(layout, layout->host.buckets[b], v_dev, sc, stream);
     if (rc != ADAM_MINI_OK) return rc;
+    if (ev) AM_HIP(hipEventRecord(ev[1], stream));
   }
+  if (timed) layout->profile_used++;
   AM_HIP(hipGetLastError());
+  return ADAM_MINI_OK;
+}
+
+uint32_t adam_mini_num_buckets(const adam_mini_layout* layout) {
+  return layout ? (uint32_t)layout->host.buckets.size() : 0;
+}
+
+int adam_mini_profile_enable(adam_mini_layout* layout, uint32_t max_steps) {
+  if (!layout) return ADAM_MINI_INVALID_ARG;
+  if (layout->device < 0) return ADAM_MINI_NO_DEVICE;
+  if (max_steps > 4096) return ADAM_MINI_INVALID_ARG;
+  DeviceGuard guard;
+  int rc = guard.enter(layout->device);
+  if (rc != ADAM_MINI_OK) return rc;
+  for (hipEvent_t e : layout->events) (void)hipEventDestroy(e);
+  layout->events.clear();
+  layout->profile_capacity = 0;
+  layout->profile_used = 0;
+  const size_t nb = layout->host.buckets.size();
+  layout->bucket_ms.assign(nb, 0.0);
+  layout->bucket_launches.assign(nb, 0);
+  if (max_steps == 0) return ADAM_MINI_OK;
+  try {
+    layout->events.reserve((size_t)max_steps * nb * 2);
+  } catch (const std::bad_alloc&) {
+    return ADAM_MINI_OUT_OF_MEMORY;
+  }
+  for (size_t i = 0; i < (size_t)max_steps * nb * 2; ++i) {
+    hipEvent_t e;
+    AM_HIP(hipEventCreate(&e));
+    layout->events.push_back(e);
+  }
+  layout->profile_capacity = max_steps;
+  return ADAM_MINI_OK;
+}
+
+int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out, uint32_t capacity) {
+  if (!layout || (!out && capacity > 0)) return ADAM_MINI_INVALID_ARG;
+  const size_t nb = layout->host.buckets.size();
+  if (layout->profile_used > 0) {
+    DeviceGuard guard;
+    int rc = guard.enter(layout->device);
+    if (rc != ADAM_MINI_OK) return rc;
+    for (uint32_t s = 0; s < layout->profile_used; ++s) {
+      for (size_t b = 0; b < nb; ++b) {
+        hipEvent_t* ev = &layout->events[((size_t)s * nb + b) * 2];
+        AM_HIP(hipEventSynchronize(ev[1]));
+        float ms = 0.0f;
+        AM_HIP(hipEventElapsedTime(&ms, ev[0], ev[1]));
+        layout->bucket_ms[b] += (double)ms;
+        layout->bucket_launches[b] += 1;
+      }
+    }
+    layout->profile_used = 0;
+  }
+  const char* gname = layout->host.grad_dtype == ADAM_MINI_GRAD_BF16 ? "am_bf16" : "float";
+  for (size_t b = 0; b < nb && b < capacity; ++b) {
+    const AmBucket& bk = layout->host.buckets[b];
+    adam_mini_bucket_info& o = out[b];
+    std::memset(&o, 0, sizeof o);
+    o.family = am_path_kind(bk.var);
+    o.vec = bk.var.vec;
+    o.lanes = bk.var.lanes;
+    o.upt = bk.var.upt;
+    o.n_tensors = (uint32_t)bk.segs.size();
+    o.n_kernels = bk.var.family == AM_FAM_LARGE ? 3u : 1u;
+    o.n_items = bk.n_items;
+    for (const AmSeg& s : bk.segs) {
+      const AmTensorInfo& ti = layout->host.tensors[s.tensor];
+      o.numel += ti.numel;
+      o.n_blocks += ti.n_blocks;
+    }
+    if (b < layout->bucket_ms.size()) {
+      o.total_ms = layout->bucket_ms[b];
+      o.timed_launches = layout->bucket_launches[b];
+    }
+    const char* kname = bk.var.family == AM_FAM_ROW ? "am_row_kernel"
+                        : bk.var.family == AM_FAM_LARGE ? "am_large_update"
+                        : bk.var.family == AM_FAM_ROW_LDS ? "am_row_lds_kernel" : "am_elementwise";
+    std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d, %d, %d>", kname, gname, bk.var.vec, bk.var.lanes, bk.var.upt);
+  }
+  if (layout->profile_capacity > 0) {  // totals are "since the last read"
+    layout->bucket_ms.assign(nb, 0.0);
+    layout->bucket_launches.assign(nb, 0);
+  }
   return ADAM_MINI_OK;
 }
 
@@ -467,6 +564,11 @@ void adam_mini_destroy_layout(adam_mini_layout* layout) {
       if (layout->partials_dev) (void)hipFree(layout->partials_dev);
       if (layout->scales_dev) (void)hipFree(layout->scales_dev);
     }
+  }
+  if (!layout->events.empty()) {
+    DeviceGuard guard;
+    if (guard.enter(layout->device) == ADAM_MINI_OK)
+      for (hipEvent_t e : layout->events) (void)hipEventDestroy(e);
   }
   delete layout;
 }

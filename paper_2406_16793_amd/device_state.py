@@ -1,0 +1,42 @@
+"""Device memory of one tensor list (allocated through PyTorch) bound to the HIP
+optimizer.  Plumbing only: allocation, pointer lists, host copies."""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+
+def bf16_bits(t) -> np.ndarray:
+    """torch.bfloat16 tensor (any device) -> numpy uint16 bit patterns on the host."""
+    import torch
+    return t.detach().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def grad_to_host(t) -> np.ndarray:
+    """Gradient tensor -> host array with the same bits (float32, or uint16 for bf16)."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        return bf16_bits(t)
+    return t.detach().cpu().numpy()
+
+
+class DeviceState:
+    """params / exp_avg / grads (one flat tensor each per spec) and v on one GPU,
+    with an AdamMini optimizer bound to them.  m and v start at zero."""
+
+    def __init__(self, specs, grad_dtype: str, device: int = 0):
+        import torch
+        self.specs = list(specs)
+        self.grad_dtype = grad_dtype
+        self.dev = torch.device("cuda:%d" % device)
+        self.opt = B.AdamMini(self.specs, grad_dtype, device)
+        gdt = torch.bfloat16 if grad_dtype == "bf16" else torch.float32
+        self.p = [torch.empty(s.numel, dtype=torch.float32, device=self.dev) for s in self.specs]
+        self.m = [torch.zeros(s.numel, dtype=torch.float32, device=self.dev) for s in self.specs]
+        self.g = [torch.zeros(s.numel, dtype=gdt, device=self.dev) for s in self.specs]
+        self.v = torch.zeros(self.opt.num_blocks, dtype=torch.float32, device=self.dev)
+        self.opt.bind(self.p, self.g, self.m, self.v)
+
+    def close(self) -> None:
+        self.opt.close()

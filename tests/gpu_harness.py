@@ -7,20 +7,8 @@ import numpy as np
 import oracle as orc
 from paper_2406_16793_amd import binding as B
 from paper_2406_16793_amd import workloads
+from paper_2406_16793_amd.device_state import DeviceState as GpuRun, grad_to_host
 from paper_2406_16793_amd.partition import TensorSpec
-
-
-def bf16_bits(t):
-    """torch.bfloat16 tensor (any device) -> numpy uint16 bit patterns on the host."""
-    import torch
-    return t.detach().cpu().view(torch.int16).numpy().view(np.uint16)
-
-
-def grad_to_host(t):
-    import torch
-    if t.dtype == torch.bfloat16:
-        return bf16_bits(t)
-    return t.detach().cpu().numpy()
 
 
 def assert_state_close(name, got, want, rtol, is_v=False):
@@ -47,27 +35,6 @@ def assert_state_close(name, got, want, rtol, is_v=False):
                              % (name, int(bad.sum()), got.size, i, got[i], want[i], err[i], tol[i]))
     denom = float(np.linalg.norm(w))
     return float(np.linalg.norm(d) / denom) if denom > 0 else 0.0
-
-
-class GpuRun:
-    """Device state of one tensor list plus the HIP optimizer bound to it."""
-
-    def __init__(self, specs, grad_dtype, device=0):
-        import torch
-        self.torch = torch
-        self.specs = list(specs)
-        self.grad_dtype = grad_dtype
-        self.dev = torch.device("cuda:%d" % device)
-        self.opt = B.AdamMini(self.specs, grad_dtype, device)
-        gdt = torch.bfloat16 if grad_dtype == "bf16" else torch.float32
-        self.p = [torch.empty(s.numel, dtype=torch.float32, device=self.dev) for s in self.specs]
-        self.m = [torch.zeros(s.numel, dtype=torch.float32, device=self.dev) for s in self.specs]
-        self.g = [torch.zeros(s.numel, dtype=gdt, device=self.dev) for s in self.specs]
-        self.v = torch.zeros(self.opt.num_blocks, dtype=torch.float32, device=self.dev)
-        self.opt.bind(self.p, self.g, self.m, self.v)
-
-    def close(self):
-        self.opt.close()
 
 
 def make_specs(blocks):
