@@ -164,7 +164,7 @@ int adam_mini_step(adam_mini_layout* layout, void* const* params,
  */
 typedef struct adam_mini_bucket_info {
   int32_t family;          /* ADAM_MINI_PATH_* */
-  int32_t vec;             /* elements per 128-bit unit (4 or 8), 1 = scalar fallback */
+  int32_t vec;             /* elements per unit (4 or 8), 1 = scalar fallback */
   int32_t lanes;           /* threads cooperating on one work item */
   int32_t upt;             /* units per thread */
   uint32_t n_tensors;      /* tensors served by this bucket */
@@ -199,14 +199,20 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  * existing layout keeps the values it was built with).  They choose which kernel
  * variant serves a block size and how launches are shaped; they never change what
  * is computed beyond the order of the fp32 partial sums.  Keys (value >= 0):
- *   "subwave_max_units"  blocks of at most this many 128-bit units use 16-thread teams
+ *   "bf16_vec"           4 or 8: elements per lane and access with bf16 gradients (4: 64-bit gradient
+ *                        loads beside lane-contiguous 128-bit m / p; 8: 128-bit gradient loads)
+ *   "subwave_max_units"  blocks of at most this many units may use 16-thread teams
  *   "wave_max_units"     ... at most this many units: one 64-thread wavefront per block
- *   "wide_min_units"     ... at least this many units: 1024-thread workgroups
+ *   "team_max_lanes"     largest number of threads that may share one block (256, 512 or 1024)
+ *   "max_upt"            preferred bound on units per thread; the smallest team within it is used
  *   "row_max_units"      blocks above this leave the single-pass register kernel
  *   "lds_max_bytes"      > 0: such blocks whose gradient fits in this much LDS use the LDS-staged kernel
- *   "large_chunk_upt"    units per thread of a chunk in the multi-workgroup path (4, 8, 16)
- *   "ew_upt"             units per thread of a tile in the AdamW-equivalent kernel (2, 4, 8)
+ *   "large_chunk_upt"    units per thread of a chunk in the multi-workgroup path (1, 2, 4, 8, 16)
+ *   "ew_upt"             units per thread of a tile in the AdamW-equivalent kernel (1, 2, 4, 8)
  *   "grid_cap"           > 0: cap on workgroups per launch (grid-stride loop beyond it)
+ *   "row_wg_per_cu"      > 0: cap on resident row-kernel workgroups per compute unit (bounds the bytes
+ *                        in flight; HBM efficiency drops when the chip is oversubscribed), 0 = no cap
+ *   "stream_wg_per_cu"   the same cap for the AdamW-equivalent and large-block update kernels
  *   "reset"              restore the defaults (value ignored)
  * Returns ADAM_MINI_INVALID_ARG for an unknown key or a negative value.
  */

@@ -75,12 +75,42 @@ namespace {
 // ---------------------------------------------------------------------------
 // kernel dispatch: the variant lists must match am_layout.cpp
 // ---------------------------------------------------------------------------
-#define AM_ROW_VARIANTS(X)                                                                        \
-  X(16, 1) X(16, 2) X(16, 4) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(64, 16) X(256, 1) X(256, 2)    \
-  X(256, 3) X(256, 4) X(256, 6) X(256, 8) X(256, 12) X(256, 16) X(1024, 1) X(1024, 2) X(1024, 3) \
-  X(1024, 4)
-#define AM_LARGE_VARIANTS(X) X(256, 4) X(256, 8) X(256, 16)
-#define AM_EW_VARIANTS(X) X(256, 2) X(256, 4) X(256, 8)
+#define AM_ROW_VARIANTS(X)                                                                              \
+  X(16, 1) X(16, 2) X(16, 4)                                                                            \
+  X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(64, 16)                                                         \
+  X(256, 1) X(256, 2) X(256, 3) X(256, 4) X(256, 6) X(256, 8) X(256, 12) X(256, 16)                     \
+  X(512, 1) X(512, 2) X(512, 3) X(512, 4) X(512, 6) X(512, 8)                                           \
+  X(1024, 1) X(1024, 2) X(1024, 3) X(1024, 4) X(1024, 6)
+#define AM_LARGE_VARIANTS(X) X(256, 1) X(256, 2) X(256, 4) X(256, 8) X(256, 16)
+#define AM_EW_VARIANTS(X) X(256, 1) X(256, 2) X(256, 4) X(256, 8)
+
+// Does the instantiation exist?  (Register-heavy combinations are never chosen by the layout builder
+// and are compiled out.)
+constexpr bool am_row_ok(int vec, int lanes, int upt) {
+  return upt * vec * 3 + 34 <= (lanes >= 1024 ? 128 : 256);
+}
+
+// Dynamic LDS bytes that leave room for exactly `cap` workgroups per CU (0 = no cap).  The kernels
+// never touch this allocation: it only bounds how many workgroups, and so how many bytes in flight,
+// a compute unit holds at once.
+constexpr size_t kLdsPerCu = 160 * 1024;
+size_t lds_for_cap(int64_t cap) {
+  if (cap <= 0) return 0;
+  if (cap > 32) cap = 32;
+  return kLdsPerCu / (size_t)cap - 1024;  // 1 KiB slack for the kernel's own static LDS
+}
+
+template <typename K>
+int allow_big_lds(K kernel) {
+  static thread_local const void* done[256];
+  static thread_local int n_done = 0;
+  const void* key = (const void*)kernel;
+  for (int i = 0; i < n_done; ++i)
+    if (done[i] == key) return ADAM_MINI_OK;
+  AM_HIP(hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsPerCu - 1024)));
+  if (n_done < 256) done[n_done++] = key;
+  return ADAM_MINI_OK;
+}
 
 uint32_t grid_for(uint64_t groups, const AmTuning& t) {
   uint64_t g = groups;
@@ -95,12 +125,19 @@ int launch_row(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, floa
   const uint32_t n_items = (uint32_t)bk.n_items;
   const uint32_t n_segs = (uint32_t)bk.segs.size();
 #define X(L, U)                                                                                         \
-  if (var.lanes == L && var.upt == U) {                                                                 \
-    constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                                   \
-    const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                                \
-    hipLaunchKernelGGL((am_row_kernel<G, VEC, L, U>), dim3(grid), dim3(WG), 0, stream, segs, n_segs,    \
-                       n_items, v, sc);                                                                 \
-    return ADAM_MINI_OK;                                                                                \
+  if constexpr (am_row_ok(VEC, L, U)) {                                                                 \
+    if (var.lanes == L && var.upt == U) {                                                               \
+      constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                                 \
+      const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                              \
+      const size_t lds = lds_for_cap(t.row_wg_per_cu);                                                  \
+      if (lds > 0) {                                                                                    \
+        const int rc_ = allow_big_lds(am_row_kernel<G, VEC, L, U>);                                     \
+        if (rc_ != ADAM_MINI_OK) return rc_;                                                            \
+      }                                                                                                 \
+      hipLaunchKernelGGL((am_row_kernel<G, VEC, L, U>), dim3(grid), dim3(WG), lds, stream, segs,        \
+                         n_segs, n_items, v, sc);                                                       \
+      return ADAM_MINI_OK;                                                                              \
+    }                                                                                                   \
   }
   AM_ROW_VARIANTS(X)
 #undef X
@@ -139,7 +176,12 @@ int launch_large(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, fl
                        n_items, partials);                                                               \
     hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, segs, n_segs, n_lblocks,    \
                        (const float*)partials, v, scales, sc);                                           \
-    hipLaunchKernelGGL((am_large_update<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,    \
+    const size_t lds = lds_for_cap(t.stream_wg_per_cu);                                                  \
+    if (lds > 0) {                                                                                       \
+      const int rc_ = allow_big_lds(am_large_update<G, VEC, L, U>);                                      \
+      if (rc_ != ADAM_MINI_OK) return rc_;                                                               \
+    }                                                                                                    \
+    hipLaunchKernelGGL((am_large_update<G, VEC, L, U>), dim3(grid), dim3(L), lds, stream, segs, n_segs,  \
                        n_items, (const float*)scales, sc);                                               \
     return ADAM_MINI_OK;                                                                                 \
   }
@@ -173,8 +215,13 @@ int launch_elementwise(const AmVariant& var, const AmBucket& bk, const AmSeg* se
   const uint32_t grid = grid_for(bk.n_items, t);
 #define X(L, U)                                                                                       \
   if (var.lanes == L && var.upt == U) {                                                               \
-    hipLaunchKernelGGL((am_elementwise<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,  \
-                       n_items, v, sc);                                                               \
+    const size_t lds = lds_for_cap(t.stream_wg_per_cu);                                               \
+    if (lds > 0) {                                                                                    \
+      const int rc_ = allow_big_lds(am_elementwise<G, VEC, L, U>);                                    \
+      if (rc_ != ADAM_MINI_OK) return rc_;                                                            \
+    }                                                                                                 \
+    hipLaunchKernelGGL((am_elementwise<G, VEC, L, U>), dim3(grid), dim3(L), lds, stream, segs,        \
+                       n_segs, n_items, v, sc);                                                       \
     return ADAM_MINI_OK;                                                                              \
   }
   AM_EW_VARIANTS(X)
@@ -200,10 +247,31 @@ int launch_elementwise_ids(const AmVariant& var, const AmBucket& bk, const AmSeg
 }
 
 // Dispatch on (gradient type, vec) -> template arguments.
-template <typename F32Fn, typename Bf16Fn, typename ScalarF32Fn, typename ScalarBf16Fn>
-int by_type(int grad_dtype, int vec, F32Fn f32, Bf16Fn bf16, ScalarF32Fn sf32, ScalarBf16Fn sbf16) {
-  if (grad_dtype == ADAM_MINI_GRAD_F32) return vec == 1 ? sf32() : f32();
-  return vec == 1 ? sbf16() : bf16();
+template <typename G_, int VEC_>
+struct AmTag {
+  using G = G_;
+  static constexpr int VEC = VEC_;
+};
+
+template <typename F>
+int dispatch_grad(int grad_dtype, int vec, F f) {
+  if (grad_dtype == ADAM_MINI_GRAD_F32) {
+    if (vec == 4) return f(AmTag<float, 4>{});
+    if (vec == 1) return f(AmTag<float, 1>{});
+  } else {
+    if (vec == 4) return f(AmTag<am_bf16, 4>{});
+    if (vec == 8) return f(AmTag<am_bf16, 8>{});
+    if (vec == 1) return f(AmTag<am_bf16, 1>{});
+  }
+  return ADAM_MINI_INVALID_ARG;
+}
+
+template <typename F>
+int dispatch_vec(int vec, F f) {
+  if (vec == 4) return f(AmTag<void, 4>{});
+  if (vec == 8) return f(AmTag<void, 8>{});
+  if (vec == 1) return f(AmTag<void, 1>{});
+  return ADAM_MINI_INVALID_ARG;
 }
 
 int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, const AmScalars& sc,
@@ -211,30 +279,19 @@ int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, 
   const AmSeg* segs = L->segs_dev + bk.table_offset;
   const AmVariant& var = bk.var;
   const AmTuning& t = L->host.tuning;
-  const int dt = L->host.grad_dtype;
-  switch (var.family) {
-    case AM_FAM_ROW:
-      return by_type(
-          dt, var.vec, [&] { return launch_row<float, 4>(var, bk, segs, v, sc, t, stream); },
-          [&] { return launch_row<am_bf16, 8>(var, bk, segs, v, sc, t, stream); },
-          [&] { return launch_row<float, 1>(var, bk, segs, v, sc, t, stream); },
-          [&] { return launch_row<am_bf16, 1>(var, bk, segs, v, sc, t, stream); });
-    case AM_FAM_LARGE:
-      return by_type(
-          dt, var.vec,
-          [&] { return launch_large<float, 4>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); },
-          [&] { return launch_large<am_bf16, 8>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); },
-          [&] { return launch_large<float, 1>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); },
-          [&] { return launch_large<am_bf16, 1>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream); });
-    case AM_FAM_ELEMENTWISE:
-      return by_type(
-          dt, var.vec, [&] { return launch_elementwise<float, 4>(var, bk, segs, v, sc, t, stream); },
-          [&] { return launch_elementwise<am_bf16, 8>(var, bk, segs, v, sc, t, stream); },
-          [&] { return launch_elementwise<float, 1>(var, bk, segs, v, sc, t, stream); },
-          [&] { return launch_elementwise<am_bf16, 1>(var, bk, segs, v, sc, t, stream); });
-    default:
-      return ADAM_MINI_INVALID_ARG;
-  }
+  return dispatch_grad(L->host.grad_dtype, var.vec, [&](auto tag) {
+    using T = decltype(tag);
+    switch (var.family) {
+      case AM_FAM_ROW:
+        return launch_row<typename T::G, T::VEC>(var, bk, segs, v, sc, t, stream);
+      case AM_FAM_LARGE:
+        return launch_large<typename T::G, T::VEC>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream);
+      case AM_FAM_ELEMENTWISE:
+        return launch_elementwise<typename T::G, T::VEC>(var, bk, segs, v, sc, t, stream);
+      default:
+        return (int)ADAM_MINI_INVALID_ARG;
+    }
+  });
 }
 
 int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t tensor, uint64_t* ids,
@@ -242,24 +299,19 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
   const AmSeg* segs = L->segs_dev + bk.table_offset;
   const AmVariant& var = bk.var;
   const AmTuning& t = L->host.tuning;
-  const int native = L->host.grad_dtype == ADAM_MINI_GRAD_BF16 ? 8 : 4;
-  const bool scalar = var.vec == 1;
-  switch (var.family) {
-    case AM_FAM_ROW:
-      if (scalar) return launch_row_ids<1>(var, bk, segs, tensor, ids, t, stream);
-      return native == 8 ? launch_row_ids<8>(var, bk, segs, tensor, ids, t, stream)
-                         : launch_row_ids<4>(var, bk, segs, tensor, ids, t, stream);
-    case AM_FAM_LARGE:
-      if (scalar) return launch_large_ids<1>(var, bk, segs, tensor, ids, t, stream);
-      return native == 8 ? launch_large_ids<8>(var, bk, segs, tensor, ids, t, stream)
-                         : launch_large_ids<4>(var, bk, segs, tensor, ids, t, stream);
-    case AM_FAM_ELEMENTWISE:
-      if (scalar) return launch_elementwise_ids<1>(var, bk, segs, tensor, ids, t, stream);
-      return native == 8 ? launch_elementwise_ids<8>(var, bk, segs, tensor, ids, t, stream)
-                         : launch_elementwise_ids<4>(var, bk, segs, tensor, ids, t, stream);
-    default:
-      return ADAM_MINI_INVALID_ARG;
-  }
+  return dispatch_vec(var.vec, [&](auto tag) {
+    constexpr int VEC = decltype(tag)::VEC;
+    switch (var.family) {
+      case AM_FAM_ROW:
+        return launch_row_ids<VEC>(var, bk, segs, tensor, ids, t, stream);
+      case AM_FAM_LARGE:
+        return launch_large_ids<VEC>(var, bk, segs, tensor, ids, t, stream);
+      case AM_FAM_ELEMENTWISE:
+        return launch_elementwise_ids<VEC>(var, bk, segs, tensor, ids, t, stream);
+      default:
+        return (int)ADAM_MINI_INVALID_ARG;
+    }
+  });
 }
 
 // ---------------------------------------------------------------------------
@@ -313,14 +365,18 @@ int adam_mini_set_option(const char* key, int64_t value) {
   const std::string k(key);
   if (k == "reset") { g_tuning = AmTuning(); return ADAM_MINI_OK; }
   if (value < 0) return ADAM_MINI_INVALID_ARG;
-  if (k == "subwave_max_units") g_tuning.subwave_max_units = value;
+  if (k == "bf16_vec") { if (value != 4 && value != 8) return ADAM_MINI_INVALID_ARG; g_tuning.bf16_vec = value; }
+  else if (k == "subwave_max_units") g_tuning.subwave_max_units = value;
   else if (k == "wave_max_units") g_tuning.wave_max_units = value;
-  else if (k == "wide_min_units") g_tuning.wide_min_units = value;
+  else if (k == "team_max_lanes") g_tuning.team_max_lanes = value;
+  else if (k == "max_upt") g_tuning.max_upt = value;
   else if (k == "row_max_units") g_tuning.row_max_units = value;
   else if (k == "lds_max_bytes") g_tuning.lds_max_bytes = value;
   else if (k == "large_chunk_upt") g_tuning.large_chunk_upt = value;
   else if (k == "ew_upt") g_tuning.ew_upt = value;
   else if (k == "grid_cap") g_tuning.grid_cap = value;
+  else if (k == "row_wg_per_cu") g_tuning.row_wg_per_cu = value;
+  else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
   else return ADAM_MINI_INVALID_ARG;
   return ADAM_MINI_OK;
 }

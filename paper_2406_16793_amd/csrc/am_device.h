@@ -10,6 +10,7 @@
 
 typedef float am_f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int am_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int am_u32x2 __attribute__((ext_vector_type(2)));
 
 struct am_bf16 {
   uint16_t bits;
@@ -90,8 +91,20 @@ __device__ __forceinline__ void am_load_grad(const void* __restrict__ base, uint
     uint16_t h = *src;
 #endif
     out[0] = am_bits_to_f32(((uint32_t)h) << 16);
+  } else if constexpr (VEC == 4) {
+    // 64-bit load: four bf16 values next to the four fp32 values of m and p the lane owns
+    const am_u32x2* src = reinterpret_cast<const am_u32x2*>(reinterpret_cast<const uint16_t*>(base) + e);
+#if AM_STREAMING
+    am_u32x2 t = __builtin_nontemporal_load(src);
+#else
+    am_u32x2 t = *src;
+#endif
+    out[0] = am_bits_to_f32(t.x << 16);  // little endian: low half is the earlier element
+    out[1] = am_bits_to_f32(t.x & 0xffff0000u);
+    out[2] = am_bits_to_f32(t.y << 16);
+    out[3] = am_bits_to_f32(t.y & 0xffff0000u);
   } else {
-    static_assert(VEC == 8, "bf16 gradients are read 8 at a time (128 bits)");
+    static_assert(VEC == 8, "bf16 gradients are read 1, 4 or 8 at a time");
     const am_u32x4* src = reinterpret_cast<const am_u32x4*>(reinterpret_cast<const uint16_t*>(base) + e);
 #if AM_STREAMING
     am_u32x4 t = __builtin_nontemporal_load(src);

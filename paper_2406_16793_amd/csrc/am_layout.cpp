@@ -8,26 +8,42 @@
 
 namespace {
 
-struct RowChoice {
-  int lanes;
-  int upt;
-};
-
 // Row-kernel instantiations that exist (must match AM_ROW_VARIANTS in adam_mini.hip).
-const RowChoice kSubwave[] = {{16, 1}, {16, 2}, {16, 4}};
-const RowChoice kWave[] = {{64, 1}, {64, 2}, {64, 4}, {64, 8}, {64, 16}};
-const RowChoice kGroup[] = {{256, 1}, {256, 2}, {256, 3}, {256, 4}, {256, 6}, {256, 8}, {256, 12}, {256, 16}};
-const RowChoice kWide[] = {{1024, 1}, {1024, 2}, {1024, 3}, {1024, 4}};
+const int kLanes[] = {16, 64, 256, 512, 1024};
+const int kUpt16[] = {1, 2, 4};
+const int kUpt64[] = {1, 2, 4, 8, 16};
+const int kUpt256[] = {1, 2, 3, 4, 6, 8, 12, 16};
+const int kUpt512[] = {1, 2, 3, 4, 6, 8};
+const int kUpt1024[] = {1, 2, 3, 4, 6};
 
-template <size_t N>
-bool pick(const RowChoice (&tab)[N], uint64_t units, RowChoice* out) {
-  for (size_t i = 0; i < N; ++i) {
-    if ((uint64_t)tab[i].lanes * (uint64_t)tab[i].upt >= units) {
-      *out = tab[i];
-      return true;
-    }
+// Register budget: a unit costs 3*vec data registers (g, m, p); 1024-thread workgroups
+// get 128 registers per lane, smaller ones 256.
+bool fits_registers(int vec, int lanes, int upt) {
+  const int budget = lanes >= 1024 ? 128 : 256;
+  return upt * vec * 3 + 34 <= budget;
+}
+
+// Smallest instantiated upt >= need for a team of `lanes`, or 0.
+int round_up_upt(int lanes, uint64_t need, int vec) {
+  const int* tab = nullptr;
+  size_t n = 0;
+  switch (lanes) {
+    case 16: tab = kUpt16; n = sizeof kUpt16 / sizeof(int); break;
+    case 64: tab = kUpt64; n = sizeof kUpt64 / sizeof(int); break;
+    case 256: tab = kUpt256; n = sizeof kUpt256 / sizeof(int); break;
+    case 512: tab = kUpt512; n = sizeof kUpt512 / sizeof(int); break;
+    case 1024: tab = kUpt1024; n = sizeof kUpt1024 / sizeof(int); break;
+    default: return 0;
   }
-  return false;
+  for (size_t i = 0; i < n; ++i)
+    if ((uint64_t)tab[i] >= need) return fits_registers(vec, lanes, tab[i]) ? tab[i] : 0;
+  return 0;
+}
+
+bool lanes_allowed(int lanes, uint64_t units, const AmTuning& t) {
+  if (lanes == 16) return units <= (uint64_t)t.subwave_max_units;
+  if (lanes == 64) return units <= (uint64_t)t.wave_max_units;
+  return lanes <= t.team_max_lanes || lanes == 256;
 }
 
 bool same_variant(const AmVariant& a, const AmVariant& b) {
@@ -47,35 +63,38 @@ int am_path_kind(const AmVariant& v) {
 
 AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel, uint64_t v_first,
                             const AmTuning& t) {
-  const int native = grad_dtype == ADAM_MINI_GRAD_BF16 ? 8 : 4;
+  const int native = grad_dtype == ADAM_MINI_GRAD_BF16 ? (t.bf16_vec == 8 ? 8 : 4) : 4;
   AmVariant var{};
   if (block_numel == 1) {
     // AdamW-equivalent: dense v.  128-bit access needs whole units and a 16-byte aligned v slice.
     var.family = AM_FAM_ELEMENTWISE;
     var.vec = (numel % (uint64_t)native == 0 && v_first % 4 == 0) ? native : 1;
     var.lanes = 256;
-    var.upt = (t.ew_upt == 2 || t.ew_upt == 8) ? (int)t.ew_upt : 4;
+    var.upt = (t.ew_upt == 1 || t.ew_upt == 2 || t.ew_upt == 8) ? (int)t.ew_upt : 4;
     return var;
   }
-  // Every block starts on a 16-byte boundary iff block_numel is a whole number of units.
+  // Every block starts on a 16-byte boundary iff block_numel is a whole number of units
+  // (8-byte gradient words of a 4-element bf16 unit are then aligned as well).
   var.vec = (block_numel % (uint64_t)native == 0) ? native : 1;
   const uint64_t units = block_numel / (uint64_t)var.vec;
-  RowChoice c{};
-  bool found = false;
   if (units <= (uint64_t)t.row_max_units) {
-    if (units <= (uint64_t)t.subwave_max_units) found = pick(kSubwave, units, &c);
-    if (!found && units <= (uint64_t)t.wave_max_units) found = pick(kWave, units, &c);
-    // 1024 threads leave 128 registers per lane: 4 units of 8 elements do not fit
-    const bool wide_ok = !(var.vec == 8 && units > 3 * 1024);
-    if (!found && wide_ok && units >= (uint64_t)t.wide_min_units) found = pick(kWide, units, &c);
-    if (!found) found = pick(kGroup, units, &c);
-    if (!found && wide_ok) found = pick(kWide, units, &c);
-  }
-  if (found) {
-    var.family = AM_FAM_ROW;
-    var.lanes = c.lanes;
-    var.upt = c.upt;
-    return var;
+    // first choice: the smallest team whose units per thread stay within max_upt
+    // second choice: the largest allowed team (fewest units per thread) that can hold the block
+    for (int pass = 0; pass < 2; ++pass) {
+      for (int i = 0; i < 5; ++i) {
+        const int lanes = pass == 0 ? kLanes[i] : kLanes[4 - i];
+        if (!lanes_allowed(lanes, units, t)) continue;
+        const uint64_t need = (units + (uint64_t)lanes - 1) / (uint64_t)lanes;
+        if (pass == 0 && need > (uint64_t)t.max_upt) continue;
+        const int upt = round_up_upt(lanes, need, var.vec);
+        if (upt == 0) continue;
+        if (pass == 0 && upt > t.max_upt) continue;
+        var.family = AM_FAM_ROW;
+        var.lanes = lanes;
+        var.upt = upt;
+        return var;
+      }
+    }
   }
   const uint64_t g_bytes = block_numel * (grad_dtype == ADAM_MINI_GRAD_BF16 ? 2u : 4u);
   if (t.lds_max_bytes > 0 && g_bytes <= (uint64_t)t.lds_max_bytes && var.vec > 1) {
@@ -86,7 +105,8 @@ AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel
   }
   var.family = AM_FAM_LARGE;
   var.lanes = 256;
-  var.upt = (t.large_chunk_upt == 4 || t.large_chunk_upt == 16) ? (int)t.large_chunk_upt : 8;
+  var.upt = (t.large_chunk_upt == 1 || t.large_chunk_upt == 2 || t.large_chunk_upt == 8 || t.large_chunk_upt == 16)
+                ? (int)t.large_chunk_upt : 4;
   return var;
 }
 

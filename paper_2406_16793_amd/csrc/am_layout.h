@@ -31,15 +31,21 @@ struct AmBucket {
 
 // Knobs of the variant choice (process-wide defaults; copied into a layout when it is built).
 struct AmTuning {
-  int64_t subwave_max_units = 64;   // blocks of <= this many units: 16-thread teams
-  int64_t wave_max_units = 256;     // blocks of <= this many units: one 64-thread wavefront each
-  int64_t wide_min_units = 1 << 30; // blocks of >= this many units: 1024-thread workgroups
-  int64_t row_max_units = 4096;     // blocks above this go to the multi-workgroup (LARGE) path
-  int64_t lds_max_bytes = 0;        // > 0: blocks above row_max_units whose gradient fits in this
-                                    //      many bytes of LDS use the LDS-staged single-pass kernel
-  int64_t large_chunk_upt = 8;      // LARGE: units per thread of a 256-thread chunk (4, 8 or 16)
-  int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (2, 4 or 8)
+  int64_t bf16_vec = 4;             // elements per unit with bf16 gradients: 4 (64-bit g loads, lane-contiguous
+                                    //   128-bit m / p) or 8 (128-bit g loads, m / p as two adjacent 128-bit words)
+  int64_t subwave_max_units = 64;   // blocks of <= this many units may use 16-thread teams
+  int64_t wave_max_units = 256;     // blocks of <= this many units may use one 64-thread wavefront each
+  int64_t team_max_lanes = 1024;    // largest team (threads per block) the row kernel may use
+  int64_t max_upt = 4;              // preferred upper bound on units per thread: the smallest team that
+                                    //   stays within it is chosen; exceeded only when no team fits otherwise
+  int64_t row_max_units = 1 << 30;  // blocks above this never use the single-pass register kernel
+  int64_t lds_max_bytes = 0;        // > 0: blocks that do not fit the register kernel and whose gradient fits
+                                    //      in this many bytes of LDS use the LDS-staged single-pass kernel
+  int64_t large_chunk_upt = 4;      // LARGE: units per thread of a 256-thread chunk (1, 2, 4, 8 or 16)
+  int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (1, 2, 4 or 8)
   int64_t grid_cap = 0;             // > 0: at most this many workgroups per launch (grid-stride beyond)
+  int64_t row_wg_per_cu = 3;        // > 0: resident row-kernel workgroups per compute unit are capped at this
+  int64_t stream_wg_per_cu = 2;     // > 0: same for the elementwise / large-update streaming kernels
 };
 
 struct AmHostLayout {
