@@ -1,0 +1,47 @@
+"""Full-size configurations on the GPU, in the launch configuration bench.py times.
+The oracle follows a seeded sample of whole blocks of every tensor (blocks never
+interact, so each sampled block is compared exactly as if the oracle had run the
+whole set), and size-independent properties are checked on everything."""
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _check_global_properties(run, wl):
+    import torch
+    assert bool(torch.isfinite(run.v).all()) and float(run.v.min()) >= 0.0
+    for k in (0, len(wl.specs) // 2, len(wl.specs) - 1):
+        assert bool(torch.isfinite(run.p[k]).all()) and bool(torch.isfinite(run.m[k]).all())
+    if wl.zero_row_prob > 0:
+        # row 0 of the embedding has a zero gradient at every step: m = v = 0, parameters only decayed
+        k = wl.zero_row_tensors[0]
+        cols = wl.specs[k].block_numel
+        assert float(run.m[k][:cols].abs().max()) == 0.0
+        voff = sum(s.n_blocks for s in wl.specs[:k])
+        assert float(run.v[voff]) == 0.0
+
+
+@pytest.mark.parametrize("name,steps", [("llama2_7b", 10), ("llama3_8b", 10), ("llama2_13b", 5)])
+def test_full_size_sampled_blocks(name, steps):
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import workloads
+    wl = workloads.get(name)
+    need = wl.n_params * (10 if wl.grad_dtype == "bf16" else 12) + (6 << 30)
+    total = torch.cuda.get_device_properties(0).total_memory
+    if total < need:
+        pytest.skip("needs %.0f GB of device memory, have %.0f GB" % (need / 1e9, total / 1e9))
+    _say("%s: %d params, %d blocks, %d steps" % (name, wl.n_params, wl.n_blocks, steps))
+    run, worst = H.run_sampled(wl, steps=steps, progress=_say)
+    _say("%s: worst normwise rel err over sampled blocks %.3g" % (name, worst))
+    _check_global_properties(run, wl)
+    run.close()
+    del run
+    torch.cuda.empty_cache()
