@@ -58,6 +58,7 @@ struct adam_mini_layout {
   bool device_ready = false;
   AmSeg* segs_dev = nullptr;       // all buckets' segments, concatenated
   AmSeg* segs_staging = nullptr;   // pinned host copy
+  uint32_t* keys_dev = nullptr;    // [2 * n_segs]: item_first of every segment, then lblock_first
   float* partials_dev = nullptr;   // LARGE: one float per chunk
   float* scales_dev = nullptr;     // LARGE: one float per large block
   bool tables_valid = false;       // segs_dev holds the pointers below
@@ -119,25 +120,32 @@ uint32_t grid_for(uint64_t groups, const AmTuning& t) {
   return (uint32_t)g;
 }
 
+#define AM_TAB tab.segs, tab.item_keys, tab.lblock_keys, tab.n_segs
+
+// Launch one kernel with an optional occupancy cap (see lds_for_cap).
+template <typename K, typename... Args>
+int launch_capped(K kernel, uint32_t grid, uint32_t block, int64_t cap, hipStream_t stream, Args... args) {
+  const size_t lds = lds_for_cap(cap);
+  if (lds > 0) {
+    const int rc = allow_big_lds(kernel);
+    if (rc != ADAM_MINI_OK) return rc;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), lds, stream, args...);
+  return ADAM_MINI_OK;
+}
+
 template <typename G, int VEC>
-int launch_row(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, float* v, const AmScalars& sc,
+int launch_row(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc,
                const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_segs = (uint32_t)bk.segs.size();
-#define X(L, U)                                                                                         \
-  if constexpr (am_row_ok(VEC, L, U)) {                                                                 \
-    if (var.lanes == L && var.upt == U) {                                                               \
-      constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                                 \
-      const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                              \
-      const size_t lds = lds_for_cap(t.row_wg_per_cu);                                                  \
-      if (lds > 0) {                                                                                    \
-        const int rc_ = allow_big_lds(am_row_kernel<G, VEC, L, U>);                                     \
-        if (rc_ != ADAM_MINI_OK) return rc_;                                                            \
-      }                                                                                                 \
-      hipLaunchKernelGGL((am_row_kernel<G, VEC, L, U>), dim3(grid), dim3(WG), lds, stream, segs,        \
-                         n_segs, n_items, v, sc);                                                       \
-      return ADAM_MINI_OK;                                                                              \
-    }                                                                                                   \
+#define X(L, U)                                                                                       \
+  if constexpr (am_row_ok(VEC, L, U)) {                                                               \
+    if (var.lanes == L && var.upt == U) {                                                             \
+      constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                               \
+      const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                            \
+      return launch_capped(am_row_kernel<G, VEC, L, U>, grid, WG, t.row_wg_per_cu, stream, AM_TAB,    \
+                           n_items, (uint32_t)(t.row_blocked != 0), v, sc);                           \
+    }                                                                                                 \
   }
   AM_ROW_VARIANTS(X)
 #undef X
@@ -145,16 +153,15 @@ int launch_row(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, floa
 }
 
 template <int VEC>
-int launch_row_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, uint32_t tensor, uint64_t* ids,
+int launch_row_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids,
                    const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_segs = (uint32_t)bk.segs.size();
 #define X(L, U)                                                                                       \
   if (var.lanes == L && var.upt == U) {                                                               \
     constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                                 \
     const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                              \
-    hipLaunchKernelGGL((am_row_ids<VEC, L, U>), dim3(grid), dim3(WG), 0, stream, segs, n_segs,        \
-                       n_items, tensor, ids);                                                         \
+    hipLaunchKernelGGL((am_row_ids<VEC, L, U>), dim3(grid), dim3(WG), 0, stream, AM_TAB, n_items,        \
+                       (uint32_t)(t.row_blocked != 0), tensor, ids);                                  \
     return ADAM_MINI_OK;                                                                              \
   }
   AM_ROW_VARIANTS(X)
@@ -163,27 +170,20 @@ int launch_row_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, 
 }
 
 template <typename G, int VEC>
-int launch_large(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, float* v, float* partials,
+int launch_large(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v, float* partials,
                  float* scales, const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_segs = (uint32_t)bk.segs.size();
   const uint32_t n_lblocks = (uint32_t)bk.n_lblocks;
   const uint32_t grid = grid_for(bk.n_items, t);
   const uint32_t fgrid = grid_for((bk.n_lblocks + 3) / 4, t);
-#define X(L, U)                                                                                          \
-  if (var.lanes == L && var.upt == U) {                                                                  \
-    hipLaunchKernelGGL((am_large_partial<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,   \
-                       n_items, partials);                                                               \
-    hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, segs, n_segs, n_lblocks,    \
-                       (const float*)partials, v, scales, sc);                                           \
-    const size_t lds = lds_for_cap(t.stream_wg_per_cu);                                                  \
-    if (lds > 0) {                                                                                       \
-      const int rc_ = allow_big_lds(am_large_update<G, VEC, L, U>);                                      \
-      if (rc_ != ADAM_MINI_OK) return rc_;                                                               \
-    }                                                                                                    \
-    hipLaunchKernelGGL((am_large_update<G, VEC, L, U>), dim3(grid), dim3(L), lds, stream, segs, n_segs,  \
-                       n_items, (const float*)scales, sc);                                               \
-    return ADAM_MINI_OK;                                                                                 \
+#define X(L, U)                                                                                        \
+  if (var.lanes == L && var.upt == U) {                                                                \
+    hipLaunchKernelGGL((am_large_partial<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, AM_TAB, n_items, \
+                       partials);                                                                      \
+    hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, AM_TAB, n_lblocks,           \
+                       (const float*)partials, v, scales, sc);                                         \
+    return launch_capped(am_large_update<G, VEC, L, U>, grid, L, t.stream_wg_per_cu, stream, AM_TAB,   \
+                         n_items, (const float*)scales, sc);                                           \
   }
   AM_LARGE_VARIANTS(X)
 #undef X
@@ -191,15 +191,14 @@ int launch_large(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, fl
 }
 
 template <int VEC>
-int launch_large_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, uint32_t tensor, uint64_t* ids,
+int launch_large_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids,
                      const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_segs = (uint32_t)bk.segs.size();
   const uint32_t grid = grid_for(bk.n_items, t);
 #define X(L, U)                                                                                      \
   if (var.lanes == L && var.upt == U) {                                                              \
-    hipLaunchKernelGGL((am_large_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,      \
-                       n_items, tensor, ids);                                                        \
+    hipLaunchKernelGGL((am_large_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, AM_TAB, n_items,      \
+                       tensor, ids);                                                                 \
     return ADAM_MINI_OK;                                                                             \
   }
   AM_LARGE_VARIANTS(X)
@@ -208,37 +207,28 @@ int launch_large_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs
 }
 
 template <typename G, int VEC>
-int launch_elementwise(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, float* v,
+int launch_elementwise(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v,
                        const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_segs = (uint32_t)bk.segs.size();
   const uint32_t grid = grid_for(bk.n_items, t);
 #define X(L, U)                                                                                       \
-  if (var.lanes == L && var.upt == U) {                                                               \
-    const size_t lds = lds_for_cap(t.stream_wg_per_cu);                                               \
-    if (lds > 0) {                                                                                    \
-      const int rc_ = allow_big_lds(am_elementwise<G, VEC, L, U>);                                    \
-      if (rc_ != ADAM_MINI_OK) return rc_;                                                            \
-    }                                                                                                 \
-    hipLaunchKernelGGL((am_elementwise<G, VEC, L, U>), dim3(grid), dim3(L), lds, stream, segs,        \
-                       n_segs, n_items, v, sc);                                                       \
-    return ADAM_MINI_OK;                                                                              \
-  }
+  if (var.lanes == L && var.upt == U)                                                                 \
+    return launch_capped(am_elementwise<G, VEC, L, U>, grid, L, t.stream_wg_per_cu, stream, AM_TAB,   \
+                         n_items, v, sc);
   AM_EW_VARIANTS(X)
 #undef X
   return ADAM_MINI_INVALID_ARG;
 }
 
 template <int VEC>
-int launch_elementwise_ids(const AmVariant& var, const AmBucket& bk, const AmSeg* segs, uint32_t tensor,
+int launch_elementwise_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab, uint32_t tensor,
                            uint64_t* ids, const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_segs = (uint32_t)bk.segs.size();
   const uint32_t grid = grid_for(bk.n_items, t);
 #define X(L, U)                                                                                          \
   if (var.lanes == L && var.upt == U) {                                                                  \
-    hipLaunchKernelGGL((am_elementwise_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, segs, n_segs,    \
-                       n_items, tensor, ids);                                                            \
+    hipLaunchKernelGGL((am_elementwise_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, AM_TAB, n_items,    \
+                       tensor, ids);                                                                     \
     return ADAM_MINI_OK;                                                                                 \
   }
   AM_EW_VARIANTS(X)
@@ -274,20 +264,29 @@ int dispatch_vec(int vec, F f) {
   return ADAM_MINI_INVALID_ARG;
 }
 
+AmTable bucket_table(const adam_mini_layout* L, const AmBucket& bk) {
+  AmTable tab;
+  tab.segs = L->segs_dev + bk.table_offset;
+  tab.item_keys = L->keys_dev + bk.table_offset;
+  tab.lblock_keys = L->keys_dev + L->host.n_segs + bk.table_offset;
+  tab.n_segs = (uint32_t)bk.segs.size();
+  return tab;
+}
+
 int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, const AmScalars& sc,
                        hipStream_t stream) {
-  const AmSeg* segs = L->segs_dev + bk.table_offset;
+  const AmTable tab = bucket_table(L, bk);
   const AmVariant& var = bk.var;
   const AmTuning& t = L->host.tuning;
   return dispatch_grad(L->host.grad_dtype, var.vec, [&](auto tag) {
     using T = decltype(tag);
     switch (var.family) {
       case AM_FAM_ROW:
-        return launch_row<typename T::G, T::VEC>(var, bk, segs, v, sc, t, stream);
+        return launch_row<typename T::G, T::VEC>(var, bk, tab, v, sc, t, stream);
       case AM_FAM_LARGE:
-        return launch_large<typename T::G, T::VEC>(var, bk, segs, v, L->partials_dev, L->scales_dev, sc, t, stream);
+        return launch_large<typename T::G, T::VEC>(var, bk, tab, v, L->partials_dev, L->scales_dev, sc, t, stream);
       case AM_FAM_ELEMENTWISE:
-        return launch_elementwise<typename T::G, T::VEC>(var, bk, segs, v, sc, t, stream);
+        return launch_elementwise<typename T::G, T::VEC>(var, bk, tab, v, sc, t, stream);
       default:
         return (int)ADAM_MINI_INVALID_ARG;
     }
@@ -296,18 +295,18 @@ int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, 
 
 int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t tensor, uint64_t* ids,
                       hipStream_t stream) {
-  const AmSeg* segs = L->segs_dev + bk.table_offset;
+  const AmTable tab = bucket_table(L, bk);
   const AmVariant& var = bk.var;
   const AmTuning& t = L->host.tuning;
   return dispatch_vec(var.vec, [&](auto tag) {
     constexpr int VEC = decltype(tag)::VEC;
     switch (var.family) {
       case AM_FAM_ROW:
-        return launch_row_ids<VEC>(var, bk, segs, tensor, ids, t, stream);
+        return launch_row_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
       case AM_FAM_LARGE:
-        return launch_large_ids<VEC>(var, bk, segs, tensor, ids, t, stream);
+        return launch_large_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
       case AM_FAM_ELEMENTWISE:
-        return launch_elementwise_ids<VEC>(var, bk, segs, tensor, ids, t, stream);
+        return launch_elementwise_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
       default:
         return (int)ADAM_MINI_INVALID_ARG;
     }
@@ -319,13 +318,22 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
 // ---------------------------------------------------------------------------
 int ensure_device_state(adam_mini_layout* L) {
   if (L->device_ready) return ADAM_MINI_OK;
-  const size_t seg_bytes = L->host.n_segs * sizeof(AmSeg);
-  AM_HIP(hipMalloc((void**)&L->segs_dev, seg_bytes));
-  AM_HIP(hipHostMalloc((void**)&L->segs_staging, seg_bytes, hipHostMallocDefault));
+  const size_t n = L->host.n_segs;
+  AM_HIP(hipMalloc((void**)&L->segs_dev, n * sizeof(AmSeg)));
+  AM_HIP(hipHostMalloc((void**)&L->segs_staging, n * sizeof(AmSeg), hipHostMallocDefault));
+  AM_HIP(hipMalloc((void**)&L->keys_dev, 2 * n * sizeof(uint32_t)));
   if (L->host.n_partials > 0) {
     AM_HIP(hipMalloc((void**)&L->partials_dev, L->host.n_partials * sizeof(float)));
     AM_HIP(hipMalloc((void**)&L->scales_dev, L->host.n_lblocks * sizeof(float)));
   }
+  // the key arrays never change: upload them once
+  std::vector<uint32_t> keys(2 * n, 0u);
+  for (const AmBucket& bk : L->host.buckets)
+    for (size_t i = 0; i < bk.segs.size(); ++i) {
+      keys[bk.table_offset + i] = bk.segs[i].item_first;
+      keys[n + bk.table_offset + i] = bk.segs[i].lblock_first;
+    }
+  AM_HIP(hipMemcpy(L->keys_dev, keys.data(), keys.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
   L->device_ready = true;
   return ADAM_MINI_OK;
 }
@@ -376,6 +384,7 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "ew_upt") g_tuning.ew_upt = value;
   else if (k == "grid_cap") g_tuning.grid_cap = value;
   else if (k == "row_wg_per_cu") g_tuning.row_wg_per_cu = value;
+  else if (k == "row_blocked") g_tuning.row_blocked = value;
   else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
   else return ADAM_MINI_INVALID_ARG;
   return ADAM_MINI_OK;
@@ -616,6 +625,7 @@ void adam_mini_destroy_layout(adam_mini_layout* layout) {
     DeviceGuard guard;
     if (guard.enter(layout->device) == ADAM_MINI_OK) {
       (void)hipFree(layout->segs_dev);
+      if (layout->keys_dev) (void)hipFree(layout->keys_dev);
       (void)hipHostFree(layout->segs_staging);
       if (layout->partials_dev) (void)hipFree(layout->partials_dev);
       if (layout->scales_dev) (void)hipFree(layout->scales_dev);

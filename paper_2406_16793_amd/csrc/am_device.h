@@ -12,6 +12,18 @@ typedef float am_f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int am_u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int am_u32x2 __attribute__((ext_vector_type(2)));
 
+// Pointers read out of the work tables have no known address space; all of them point to
+// device (global) memory, so say so: the loads and stores become global_* instead of flat_*.
+#define AM_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ const AM_GLOBAL T* am_global(const T* p) {
+  return (const AM_GLOBAL T*)(uintptr_t)p;
+}
+template <typename T>
+__device__ __forceinline__ AM_GLOBAL T* am_global(T* p) {
+  return (AM_GLOBAL T*)(uintptr_t)p;
+}
+
 struct am_bf16 {
   uint16_t bits;
 };
@@ -27,14 +39,14 @@ template <int VEC>
 __device__ __forceinline__ void am_load_f32(const float* __restrict__ base, uint64_t e, float (&out)[VEC]) {
   if constexpr (VEC == 1) {
 #if AM_STREAMING
-    out[0] = __builtin_nontemporal_load(base + e);
+    out[0] = __builtin_nontemporal_load(am_global(base + e));
 #else
-    out[0] = base[e];
+    out[0] = *am_global(base + e);
 #endif
   } else {
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
-      const am_f32x4* src = reinterpret_cast<const am_f32x4*>(base + e) + j;
+      const AM_GLOBAL am_f32x4* src = am_global(reinterpret_cast<const am_f32x4*>(base + e) + j);
 #if AM_STREAMING
       am_f32x4 t = __builtin_nontemporal_load(src);
 #else
@@ -52,9 +64,9 @@ template <int VEC>
 __device__ __forceinline__ void am_store_f32(float* __restrict__ base, uint64_t e, const float (&in)[VEC]) {
   if constexpr (VEC == 1) {
 #if AM_STREAMING
-    __builtin_nontemporal_store(in[0], base + e);
+    __builtin_nontemporal_store(in[0], am_global(base + e));
 #else
-    base[e] = in[0];
+    *am_global(base + e) = in[0];
 #endif
   } else {
 #pragma unroll
@@ -64,7 +76,7 @@ __device__ __forceinline__ void am_store_f32(float* __restrict__ base, uint64_t 
       t.y = in[4 * j + 1];
       t.z = in[4 * j + 2];
       t.w = in[4 * j + 3];
-      am_f32x4* dst = reinterpret_cast<am_f32x4*>(base + e) + j;
+      AM_GLOBAL am_f32x4* dst = am_global(reinterpret_cast<am_f32x4*>(base + e) + j);
 #if AM_STREAMING
       __builtin_nontemporal_store(t, dst);
 #else
@@ -84,7 +96,7 @@ __device__ __forceinline__ void am_load_grad(const void* __restrict__ base, uint
   if constexpr (sizeof(G) == 4) {
     am_load_f32<VEC>(reinterpret_cast<const float*>(base), e, out);
   } else if constexpr (VEC == 1) {
-    const uint16_t* src = reinterpret_cast<const uint16_t*>(base) + e;
+    const AM_GLOBAL uint16_t* src = am_global(reinterpret_cast<const uint16_t*>(base) + e);
 #if AM_STREAMING
     uint16_t h = __builtin_nontemporal_load(src);
 #else
@@ -93,7 +105,8 @@ __device__ __forceinline__ void am_load_grad(const void* __restrict__ base, uint
     out[0] = am_bits_to_f32(((uint32_t)h) << 16);
   } else if constexpr (VEC == 4) {
     // 64-bit load: four bf16 values next to the four fp32 values of m and p the lane owns
-    const am_u32x2* src = reinterpret_cast<const am_u32x2*>(reinterpret_cast<const uint16_t*>(base) + e);
+    const AM_GLOBAL am_u32x2* src =
+        am_global(reinterpret_cast<const am_u32x2*>(reinterpret_cast<const uint16_t*>(base) + e));
 #if AM_STREAMING
     am_u32x2 t = __builtin_nontemporal_load(src);
 #else
@@ -105,7 +118,8 @@ __device__ __forceinline__ void am_load_grad(const void* __restrict__ base, uint
     out[3] = am_bits_to_f32(t.y & 0xffff0000u);
   } else {
     static_assert(VEC == 8, "bf16 gradients are read 1, 4 or 8 at a time");
-    const am_u32x4* src = reinterpret_cast<const am_u32x4*>(reinterpret_cast<const uint16_t*>(base) + e);
+    const AM_GLOBAL am_u32x4* src =
+        am_global(reinterpret_cast<const am_u32x4*>(reinterpret_cast<const uint16_t*>(base) + e));
 #if AM_STREAMING
     am_u32x4 t = __builtin_nontemporal_load(src);
 #else
@@ -178,19 +192,11 @@ __device__ __forceinline__ double am_wave_sum_f64(double x) {
 // ---------------------------------------------------------------------------
 // work-table lookup: last segment whose first key is <= key
 // ---------------------------------------------------------------------------
-struct AmByItem {
-  __device__ __forceinline__ static uint64_t key(const AmSeg& s) { return s.item_first; }
-};
-struct AmByLargeBlock {
-  __device__ __forceinline__ static uint64_t key(const AmSeg& s) { return s.lblock_first; }
-};
-
-template <typename Key>
-__device__ __forceinline__ uint32_t am_find_seg(const AmSeg* __restrict__ segs, uint32_t n_segs, uint64_t key) {
+__device__ __forceinline__ uint32_t am_find_seg(const uint32_t* __restrict__ keys, uint32_t n_segs, uint32_t key) {
   uint32_t lo = 0, hi = n_segs;
   while (hi - lo > 1) {
     const uint32_t mid = (lo + hi) >> 1;
-    if (Key::key(segs[mid]) <= key) lo = mid; else hi = mid;
+    if (keys[mid] <= key) lo = mid; else hi = mid;
   }
   return lo;
 }

@@ -17,6 +17,13 @@
 
 #include "am_device.h"
 
+// A bucket's tables as kernel parameters.  They are separate restrict-qualified pointers (not a
+// struct) so the compiler knows they are read-only and keeps the table walk on scalar loads.
+#define AM_TABLE_PARAMS                                                                       \
+  const AmSeg* __restrict__ segs, const uint32_t* __restrict__ item_keys,                     \
+      const uint32_t* __restrict__ lblock_keys, uint32_t n_segs
+#define AM_TABLE_ARGS segs, item_keys, lblock_keys, n_segs
+
 // ===========================================================================
 // ROW family
 // ===========================================================================
@@ -30,14 +37,13 @@ struct AmRowGeom {
 // What a team needs to know about its work item.
 struct AmRowItem {
   const AmSeg* seg;
-  uint64_t block;  // block index inside the tensor
+  uint32_t block;  // block index inside the tensor
   uint64_t elem0;  // first element of the block inside the tensor
   bool active;
 };
 
 template <int LANES>
-__device__ __forceinline__ AmRowItem am_row_decode(const AmSeg* __restrict__ segs, uint32_t n_segs,
-                                                   uint32_t n_items, uint32_t first_item) {
+__device__ __forceinline__ AmRowItem am_row_decode(AM_TABLE_PARAMS, uint32_t n_items, uint32_t first_item) {
   const uint32_t team = threadIdx.x / LANES;
   uint32_t item = first_item + team;
   AmRowItem it;
@@ -45,29 +51,33 @@ __device__ __forceinline__ AmRowItem am_row_decode(const AmSeg* __restrict__ seg
   if (!it.active) item = n_items - 1;  // keep the lookup in range; loads and stores are masked
   // a team of whole wavefronts shares its item: keep the table walk on the scalar unit
   if constexpr (LANES >= 64) item = __builtin_amdgcn_readfirstlane(item);
-  const uint32_t s = am_find_seg<AmByItem>(segs, n_segs, item);
+  const uint32_t s = am_find_seg(item_keys, n_segs, item);
   it.seg = segs + s;
-  it.block = (uint64_t)item - it.seg->item_first;
-  it.elem0 = it.block * it.seg->block_numel;
+  it.block = item - item_keys[s];
+  it.elem0 = (uint64_t)it.block * it.seg->block_numel;
   return it;
 }
 
-// unit index handled by a team lane at unroll step k
-template <int LANES>
-__device__ __forceinline__ uint64_t am_row_unit(int k) {
-  return (uint64_t)(threadIdx.x % LANES) + (uint64_t)k * LANES;
+// Unit index handled by a team lane at unroll step k.  Strided: step k of the whole team covers one
+// contiguous run of LANES units.  Blocked: each wavefront owns UPT*64 consecutive units, step k
+// covering 64 of them, so a wavefront's accesses stay inside one contiguous span of the block.
+template <int LANES, int UPT>
+__device__ __forceinline__ uint64_t am_row_unit(int k, uint32_t blocked) {
+  const uint32_t lane = threadIdx.x % LANES;
+  if (LANES >= 64 && blocked) return (uint64_t)((lane >> 6) * UPT + k) * 64 + (lane & 63);
+  return (uint64_t)lane + (uint64_t)k * LANES;
 }
 
 template <typename G, int VEC, int LANES, int UPT>
-__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(const AmSeg* __restrict__ segs,
-                                                                      uint32_t n_segs, uint32_t n_items,
-                                                                      float* __restrict__ v, AmScalars sc) {
+__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(AM_TABLE_PARAMS, uint32_t n_items,
+                                                                      uint32_t blocked, float* __restrict__ v,
+                                                                      AmScalars sc) {
   using Geom = AmRowGeom<LANES>;
   // slot [parity][w] = sum of wavefront w; slot [parity][WAVES] = the block's old v
   __shared__ float xch[2][(Geom::WAVES > 1 ? Geom::WAVES : 1) + 1];
   uint32_t parity = 0;
   for (uint32_t first = blockIdx.x * Geom::TEAMS; first < n_items; first += gridDim.x * Geom::TEAMS, parity ^= 1u) {
-    const AmRowItem it = am_row_decode<LANES>(segs, n_segs, n_items, first);
+    const AmRowItem it = am_row_decode<LANES>(AM_TABLE_ARGS, n_items, first);
     const AmSeg& S = *it.seg;
     const uint64_t units = S.units_per_block;
     const uint64_t v_idx = S.v_first + it.block;
@@ -83,7 +93,7 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(const AmSe
     }
 #pragma unroll
     for (int k = 0; k < UPT; ++k) {
-      const uint64_t u = am_row_unit<LANES>(k);
+      const uint64_t u = am_row_unit<LANES, UPT>(k, blocked);
       if (it.active && u < units) {
         const uint64_t e = it.elem0 + u * VEC;
         am_load_grad<G, VEC>(S.g, e, gv[k]);
@@ -124,7 +134,7 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(const AmSe
 
 #pragma unroll
     for (int k = 0; k < UPT; ++k) {
-      const uint64_t u = am_row_unit<LANES>(k);
+      const uint64_t u = am_row_unit<LANES, UPT>(k, blocked);
       if (it.active && u < units) {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale, decay, sc);
@@ -138,18 +148,19 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(const AmSe
 
 // Same walk, writing the v index of every element of tensor `tensor`.
 template <int VEC, int LANES, int UPT>
-__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(const AmSeg* __restrict__ segs, uint32_t n_segs,
-                                                                   uint32_t n_items, uint32_t tensor,
+__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_TABLE_PARAMS,
+                                                                   uint32_t n_items, uint32_t blocked,
+                                                                   uint32_t tensor,
                                                                    uint64_t* __restrict__ ids) {
   using Geom = AmRowGeom<LANES>;
   for (uint32_t first = blockIdx.x * Geom::TEAMS; first < n_items; first += gridDim.x * Geom::TEAMS) {
-    const AmRowItem it = am_row_decode<LANES>(segs, n_segs, n_items, first);
+    const AmRowItem it = am_row_decode<LANES>(AM_TABLE_ARGS, n_items, first);
     const AmSeg& S = *it.seg;
     if (!it.active || S.tensor != tensor) continue;
     const uint64_t v_idx = S.v_first + it.block;
 #pragma unroll
     for (int k = 0; k < UPT; ++k) {
-      const uint64_t u = am_row_unit<LANES>(k);
+      const uint64_t u = am_row_unit<LANES, UPT>(k, blocked);
       if (u < S.units_per_block) {
         const uint64_t e = it.elem0 + u * VEC;
 #pragma unroll
@@ -164,23 +175,22 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(const AmSeg* 
 // ===========================================================================
 struct AmChunkItem {
   const AmSeg* seg;
-  uint64_t block;   // block index inside the tensor
+  uint32_t block;   // block index inside the tensor
   uint64_t elem0;   // first element of the block inside the tensor
   uint64_t unit0;   // first unit of the chunk inside the block
-  uint64_t lblock;  // index of the block among the bucket's large blocks
+  uint32_t lblock;  // index of the block among the bucket's large blocks
 };
 
-__device__ __forceinline__ AmChunkItem am_chunk_decode(const AmSeg* __restrict__ segs, uint32_t n_segs,
-                                                       uint32_t item, uint32_t chunk_units) {
-  const uint32_t s = am_find_seg<AmByItem>(segs, n_segs, item);
+__device__ __forceinline__ AmChunkItem am_chunk_decode(AM_TABLE_PARAMS, uint32_t item, uint32_t chunk_units) {
+  const uint32_t s = am_find_seg(item_keys, n_segs, item);
   AmChunkItem it;
   it.seg = segs + s;
-  const uint64_t local = (uint64_t)item - it.seg->item_first;
+  const uint32_t local = item - item_keys[s];
   it.block = local / it.seg->chunks_per_block;
-  const uint64_t chunk = local - it.block * it.seg->chunks_per_block;
-  it.elem0 = it.block * it.seg->block_numel;
-  it.unit0 = chunk * chunk_units;
-  it.lblock = it.seg->lblock_first + it.block;
+  const uint32_t chunk = local - it.block * it.seg->chunks_per_block;
+  it.elem0 = (uint64_t)it.block * it.seg->block_numel;
+  it.unit0 = (uint64_t)chunk * chunk_units;
+  it.lblock = lblock_keys[s] + it.block;
   return it;
 }
 
@@ -190,12 +200,12 @@ __device__ __forceinline__ uint64_t am_chunk_unit(uint64_t unit0, int k) {
 }
 
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_large_partial(const AmSeg* __restrict__ segs, uint32_t n_segs,
+__global__ __launch_bounds__(THREADS) void am_large_partial(AM_TABLE_PARAMS,
                                                             uint32_t n_items, float* __restrict__ partials) {
   __shared__ float slots[2][THREADS / 64];
   uint32_t parity = 0;
   for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x, parity ^= 1u) {
-    const AmChunkItem it = am_chunk_decode(segs, n_segs, item, THREADS * UPT);
+    const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     float gv[UPT][VEC];
 #pragma unroll
@@ -220,19 +230,19 @@ __global__ __launch_bounds__(THREADS) void am_large_partial(const AmSeg* __restr
 
 // One wavefront per large block: sums the block's chunk partials in a fixed order
 // (lane-strided, then butterfly) in double, updates v and stores the step scale.
-__global__ __launch_bounds__(256) void am_large_finalize(const AmSeg* __restrict__ segs, uint32_t n_segs,
+__global__ __launch_bounds__(256) void am_large_finalize(AM_TABLE_PARAMS,
                                                          uint32_t n_lblocks, const float* __restrict__ partials,
                                                          float* __restrict__ v, float* __restrict__ scales,
                                                          AmScalars sc) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t waves_per_grid = gridDim.x * 4;
   for (uint32_t lb = blockIdx.x * 4 + (threadIdx.x >> 6); lb < n_lblocks; lb += waves_per_grid) {
-    const uint32_t s = am_find_seg<AmByLargeBlock>(segs, n_segs, lb);
+    const uint32_t s = am_find_seg(lblock_keys, n_segs, lb);
     const AmSeg& S = segs[s];
-    const uint64_t block = (uint64_t)lb - S.lblock_first;
-    const uint64_t first = S.item_first + block * S.chunks_per_block;
+    const uint32_t block = lb - lblock_keys[s];
+    const uint32_t first = item_keys[s] + block * S.chunks_per_block;
     double acc = 0.0;
-    for (uint64_t c = lane; c < S.chunks_per_block; c += 64) acc += (double)partials[first + c];
+    for (uint32_t c = lane; c < S.chunks_per_block; c += 64) acc += (double)partials[first + c];
     acc = am_wave_sum_f64(acc);
     if (lane == 0) {
       const uint64_t v_idx = S.v_first + block;
@@ -245,11 +255,11 @@ __global__ __launch_bounds__(256) void am_large_finalize(const AmSeg* __restrict
 }
 
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_large_update(const AmSeg* __restrict__ segs, uint32_t n_segs,
+__global__ __launch_bounds__(THREADS) void am_large_update(AM_TABLE_PARAMS,
                                                            uint32_t n_items, const float* __restrict__ scales,
                                                            AmScalars sc) {
   for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const AmChunkItem it = am_chunk_decode(segs, n_segs, item, THREADS * UPT);
+    const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     const float scale = scales[it.lblock];
     const float decay = sc.lr_wd * S.wd_scale;
@@ -279,11 +289,11 @@ __global__ __launch_bounds__(THREADS) void am_large_update(const AmSeg* __restri
 }
 
 template <int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_large_ids(const AmSeg* __restrict__ segs, uint32_t n_segs,
+__global__ __launch_bounds__(THREADS) void am_large_ids(AM_TABLE_PARAMS,
                                                         uint32_t n_items, uint32_t tensor,
                                                         uint64_t* __restrict__ ids) {
   for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const AmChunkItem it = am_chunk_decode(segs, n_segs, item, THREADS * UPT);
+    const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;
     const uint64_t v_idx = S.v_first + it.block;
@@ -307,20 +317,19 @@ struct AmTileItem {
   uint64_t unit0;  // first unit of the tile inside the tensor
 };
 
-__device__ __forceinline__ AmTileItem am_tile_decode(const AmSeg* __restrict__ segs, uint32_t n_segs,
-                                                     uint32_t item, uint32_t tile_units) {
-  const uint32_t s = am_find_seg<AmByItem>(segs, n_segs, item);
+__device__ __forceinline__ AmTileItem am_tile_decode(AM_TABLE_PARAMS, uint32_t item, uint32_t tile_units) {
+  const uint32_t s = am_find_seg(item_keys, n_segs, item);
   AmTileItem it;
   it.seg = segs + s;
-  it.unit0 = ((uint64_t)item - it.seg->item_first) * tile_units;
+  it.unit0 = (uint64_t)(item - item_keys[s]) * tile_units;
   return it;
 }
 
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_elementwise(const AmSeg* __restrict__ segs, uint32_t n_segs,
+__global__ __launch_bounds__(THREADS) void am_elementwise(AM_TABLE_PARAMS,
                                                           uint32_t n_items, float* __restrict__ v, AmScalars sc) {
   for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const AmTileItem it = am_tile_decode(segs, n_segs, item, THREADS * UPT);
+    const AmTileItem it = am_tile_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     float* __restrict__ vt = v + S.v_first;
     const float decay = sc.lr_wd * S.wd_scale;
@@ -357,11 +366,11 @@ __global__ __launch_bounds__(THREADS) void am_elementwise(const AmSeg* __restric
 }
 
 template <int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_elementwise_ids(const AmSeg* __restrict__ segs, uint32_t n_segs,
+__global__ __launch_bounds__(THREADS) void am_elementwise_ids(AM_TABLE_PARAMS,
                                                               uint32_t n_items, uint32_t tensor,
                                                               uint64_t* __restrict__ ids) {
   for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const AmTileItem it = am_tile_decode(segs, n_segs, item, THREADS * UPT);
+    const AmTileItem it = am_tile_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;
 #pragma unroll

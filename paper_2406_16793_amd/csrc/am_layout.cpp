@@ -150,10 +150,10 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     s.g = nullptr;
     s.m = nullptr;
     s.v_first = ti.v_first;
-    s.item_first = bk.n_items;
+    s.item_first = (uint32_t)bk.n_items;
     s.block_numel = d.block_numel;
     s.chunks_per_block = 1;
-    s.lblock_first = bk.n_lblocks;
+    s.lblock_first = (uint32_t)bk.n_lblocks;
     s.tensor = k;
     s.wd_scale = d.wd_scale;
     uint64_t items = 0;
@@ -166,8 +166,10 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       items = ti.n_blocks;
     } else {
       s.units_per_block = d.block_numel / (uint64_t)var.vec;
-      s.chunks_per_block = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
-      items = ti.n_blocks * s.chunks_per_block;
+      const uint64_t cpb = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
+      if (cpb >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
+      s.chunks_per_block = (uint32_t)cpb;
+      items = ti.n_blocks * cpb;
       bk.n_lblocks += ti.n_blocks;
     }
     bk.n_items += items;

@@ -23,13 +23,23 @@ struct AmSeg {
   const void* g;          // grads (fp32 or bf16)
   float* m;               // first moment (fp32)
   uint64_t v_first;       // index of the tensor's first scalar in v
-  uint64_t item_first;    // number of work items of the bucket before this tensor
   uint64_t block_numel;   // elements per block (ELEMENTWISE: numel of the tensor)
   uint64_t units_per_block;  // block_numel / VEC (ELEMENTWISE: ceil(numel / VEC))
-  uint64_t chunks_per_block; // LARGE: work items per block; otherwise 1
-  uint64_t lblock_first;  // LARGE: number of large blocks of the bucket before this tensor
+  uint32_t item_first;    // number of work items of the bucket before this tensor
+  uint32_t lblock_first;  // LARGE: number of large blocks of the bucket before this tensor
+  uint32_t chunks_per_block; // LARGE: work items per block; otherwise 1
   uint32_t tensor;        // index in the caller's tensor list
   float wd_scale;         // lambda_k = weight_decay * wd_scale
+  uint32_t pad_;
+};
+
+// A bucket's device tables.  The two key arrays repeat item_first / lblock_first of every
+// segment densely, so the binary search of a workgroup stays inside a few cache lines.
+struct AmTable {
+  const AmSeg* segs;
+  const uint32_t* item_keys;    // [n_segs] ascending
+  const uint32_t* lblock_keys;  // [n_segs] ascending (LARGE only; otherwise zeros)
+  uint32_t n_segs;
 };
 
 // Per-step scalars, computed on the host in double and rounded once to fp32.
