@@ -170,6 +170,34 @@ int launch_row_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab,
 }
 
 template <typename G, int VEC>
+int launch_row_lds(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmTuning& t,
+                   hipStream_t stream) {
+  if constexpr (VEC == 1) {
+    return ADAM_MINI_INVALID_ARG;  // the layout builder never stages scalar-unit blocks
+  } else {
+    const uint32_t n_items = (uint32_t)bk.n_items;
+    const uint32_t grid = grid_for(bk.n_items, t);
+    const size_t lds = (size_t)((bk.lds_bytes + 15) & ~15ull);
+    if (lds > kLdsPerCu - 1024) return ADAM_MINI_INVALID_ARG;
+    const int rc = allow_big_lds(am_row_lds_kernel<G, VEC>);
+    if (rc != ADAM_MINI_OK) return rc;
+    hipLaunchKernelGGL((am_row_lds_kernel<G, VEC>), dim3(grid), dim3(kLdsRowThreads), lds, stream, AM_TAB, n_items,
+                       v, sc);
+    return ADAM_MINI_OK;
+  }
+}
+
+template <int VEC>
+int launch_row_lds_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmTuning& t,
+                       hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t grid = grid_for(bk.n_items, t);
+  hipLaunchKernelGGL((am_row_lds_ids<VEC>), dim3(grid), dim3(kLdsRowThreads), 0, stream, AM_TAB, n_items, tensor,
+                     ids);
+  return ADAM_MINI_OK;
+}
+
+template <typename G, int VEC>
 int launch_large(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v, float* partials,
                  float* scales, const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
@@ -283,6 +311,8 @@ int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, 
     switch (var.family) {
       case AM_FAM_ROW:
         return launch_row<typename T::G, T::VEC>(var, bk, tab, v, sc, t, stream);
+      case AM_FAM_ROW_LDS:
+        return launch_row_lds<typename T::G, T::VEC>(bk, tab, v, sc, t, stream);
       case AM_FAM_LARGE:
         return launch_large<typename T::G, T::VEC>(var, bk, tab, v, L->partials_dev, L->scales_dev, sc, t, stream);
       case AM_FAM_ELEMENTWISE:
@@ -303,6 +333,8 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
     switch (var.family) {
       case AM_FAM_ROW:
         return launch_row_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
+      case AM_FAM_ROW_LDS:
+        return launch_row_lds_ids<VEC>(bk, tab, tensor, ids, t, stream);
       case AM_FAM_LARGE:
         return launch_large_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
       case AM_FAM_ELEMENTWISE:
@@ -379,7 +411,10 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "team_max_lanes") g_tuning.team_max_lanes = value;
   else if (k == "max_upt") g_tuning.max_upt = value;
   else if (k == "row_max_units") g_tuning.row_max_units = value;
-  else if (k == "lds_max_bytes") g_tuning.lds_max_bytes = value;
+  else if (k == "lds_max_bytes") {
+    if (value > (int64_t)(kLdsPerCu - 1024)) return ADAM_MINI_INVALID_ARG;
+    g_tuning.lds_max_bytes = value;
+  }
   else if (k == "large_chunk_upt") g_tuning.large_chunk_upt = value;
   else if (k == "ew_upt") g_tuning.ew_upt = value;
   else if (k == "grid_cap") g_tuning.grid_cap = value;
@@ -610,7 +645,10 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
     const char* kname = bk.var.family == AM_FAM_ROW ? "am_row_kernel"
                         : bk.var.family == AM_FAM_LARGE ? "am_large_update"
                         : bk.var.family == AM_FAM_ROW_LDS ? "am_row_lds_kernel" : "am_elementwise";
-    std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d, %d, %d>", kname, gname, bk.var.vec, bk.var.lanes, bk.var.upt);
+    if (bk.var.family == AM_FAM_ROW_LDS)
+      std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d>", kname, gname, bk.var.vec);
+    else
+      std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d, %d, %d>", kname, gname, bk.var.vec, bk.var.lanes, bk.var.upt);
   }
   if (layout->profile_capacity > 0) {  // totals are "since the last read"
     layout->bucket_ms.assign(nb, 0.0);

@@ -88,50 +88,51 @@ __device__ __forceinline__ void am_store_f32(float* __restrict__ base, uint64_t 
 
 __device__ __forceinline__ float am_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b); }
 
-// Gradient load, widened to fp32.  bf16 is the upper half of an fp32 word, so the
-// widening is a shift (exact).  keep_cached: the caller will read the same bytes
-// again soon (second pass of the LARGE path), so do not mark the load streaming.
+// Gradient units.  AmRaw<G,VEC>::T is the register / LDS form of one unit as it sits in memory
+// (VEC fp32 values, or VEC bf16 values packed two to a dword); am_widen turns it into VEC floats.
+// bf16 is the upper half of an fp32 word, so widening is a shift or a mask (exact).
+template <typename G, int VEC> struct AmRaw;
+template <> struct AmRaw<float, 1> { using T = float; };
+template <> struct AmRaw<float, 4> { using T = am_f32x4; };
+template <> struct AmRaw<am_bf16, 1> { using T = uint16_t; };
+template <> struct AmRaw<am_bf16, 4> { using T = am_u32x2; };
+template <> struct AmRaw<am_bf16, 8> { using T = am_u32x4; };
+
+template <typename G, int VEC>
+__device__ __forceinline__ typename AmRaw<G, VEC>::T am_load_grad_raw(const void* __restrict__ base, uint64_t e) {
+  using T = typename AmRaw<G, VEC>::T;
+  const AM_GLOBAL T* src = am_global(reinterpret_cast<const T*>(reinterpret_cast<const G*>(base) + e));
+#if AM_STREAMING
+  return __builtin_nontemporal_load(src);
+#else
+  return *src;
+#endif
+}
+
+__device__ __forceinline__ void am_widen(float r, float (&out)[1]) { out[0] = r; }
+__device__ __forceinline__ void am_widen(am_f32x4 r, float (&out)[4]) {
+  out[0] = r.x; out[1] = r.y; out[2] = r.z; out[3] = r.w;
+}
+__device__ __forceinline__ void am_widen(uint16_t r, float (&out)[1]) { out[0] = am_bits_to_f32(((uint32_t)r) << 16); }
+__device__ __forceinline__ void am_widen(am_u32x2 r, float (&out)[4]) {
+  out[0] = am_bits_to_f32(r.x << 16);  // little endian: the low half is the earlier element
+  out[1] = am_bits_to_f32(r.x & 0xffff0000u);
+  out[2] = am_bits_to_f32(r.y << 16);
+  out[3] = am_bits_to_f32(r.y & 0xffff0000u);
+}
+__device__ __forceinline__ void am_widen(am_u32x4 r, float (&out)[8]) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    out[2 * j + 0] = am_bits_to_f32(w[j] << 16);
+    out[2 * j + 1] = am_bits_to_f32(w[j] & 0xffff0000u);
+  }
+}
+
+// Gradient load, widened to fp32.
 template <typename G, int VEC>
 __device__ __forceinline__ void am_load_grad(const void* __restrict__ base, uint64_t e, float (&out)[VEC]) {
-  if constexpr (sizeof(G) == 4) {
-    am_load_f32<VEC>(reinterpret_cast<const float*>(base), e, out);
-  } else if constexpr (VEC == 1) {
-    const AM_GLOBAL uint16_t* src = am_global(reinterpret_cast<const uint16_t*>(base) + e);
-#if AM_STREAMING
-    uint16_t h = __builtin_nontemporal_load(src);
-#else
-    uint16_t h = *src;
-#endif
-    out[0] = am_bits_to_f32(((uint32_t)h) << 16);
-  } else if constexpr (VEC == 4) {
-    // 64-bit load: four bf16 values next to the four fp32 values of m and p the lane owns
-    const AM_GLOBAL am_u32x2* src =
-        am_global(reinterpret_cast<const am_u32x2*>(reinterpret_cast<const uint16_t*>(base) + e));
-#if AM_STREAMING
-    am_u32x2 t = __builtin_nontemporal_load(src);
-#else
-    am_u32x2 t = *src;
-#endif
-    out[0] = am_bits_to_f32(t.x << 16);  // little endian: low half is the earlier element
-    out[1] = am_bits_to_f32(t.x & 0xffff0000u);
-    out[2] = am_bits_to_f32(t.y << 16);
-    out[3] = am_bits_to_f32(t.y & 0xffff0000u);
-  } else {
-    static_assert(VEC == 8, "bf16 gradients are read 1, 4 or 8 at a time");
-    const AM_GLOBAL am_u32x4* src =
-        am_global(reinterpret_cast<const am_u32x4*>(reinterpret_cast<const uint16_t*>(base) + e));
-#if AM_STREAMING
-    am_u32x4 t = __builtin_nontemporal_load(src);
-#else
-    am_u32x4 t = *src;
-#endif
-    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      out[2 * j + 0] = am_bits_to_f32(w[j] << 16);          // little endian: low half is the earlier element
-      out[2 * j + 1] = am_bits_to_f32(w[j] & 0xffff0000u);
-    }
-  }
+  am_widen(am_load_grad_raw<G, VEC>(base, e), out);
 }
 
 // ---------------------------------------------------------------------------

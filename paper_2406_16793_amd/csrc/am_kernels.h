@@ -3,6 +3,8 @@
 //   am_row_kernel        one block per team of LANES threads, whole block in registers:
 //                        loads g, m, p once, reduces sum(g^2), updates v, m, p.  Teams of 16
 //                        or 64 threads are packed several to a 256-thread workgroup.
+//   am_row_lds_kernel    one block per 1024-thread workgroup, gradient staged in LDS (blocks too big
+//                        for the registers of one workgroup, up to ~150 KB of gradient)
 //   am_large_partial     blocks too big for one workgroup: per-chunk sum(g^2)
 //   am_large_finalize    per block: fixed-order sum of its chunk partials, v update, step scale
 //   am_large_update      per chunk: m and p update with the block's step scale
@@ -167,6 +169,127 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_TABLE_PARA
         for (int j = 0; j < VEC; ++j) ids[e + j] = v_idx;
       }
     }
+  }
+}
+
+// ===========================================================================
+// ROW_LDS family: one block per 1024-thread workgroup, too big for the registers of the team
+// but small enough that its gradient fits the compute unit's 160 KB of LDS.  Pass 1 streams g
+// from HBM into LDS (as it sits in memory) while summing squares; pass 2 streams m and p,
+// taking g back from LDS.  g is read from HBM once, as in the register kernel.
+// ===========================================================================
+constexpr int kLdsRowThreads = 1024;
+constexpr int kLdsRowUnroll = 4;  // independent loads in flight per thread in either pass
+
+// unit handled by a thread at (outer step i, unroll slot j)
+__device__ __forceinline__ uint64_t am_lds_unit(uint64_t i, int j) {
+  return (i * kLdsRowUnroll + j) * kLdsRowThreads + threadIdx.x;
+}
+
+template <typename G, int VEC>
+__global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_TABLE_PARAMS, uint32_t n_items,
+                                                                    float* __restrict__ v, AmScalars sc) {
+  using Raw = typename AmRaw<G, VEC>::T;
+  extern __shared__ __attribute__((aligned(16))) unsigned char am_stage_bytes[];
+  Raw* stage = reinterpret_cast<Raw*>(am_stage_bytes);
+  __shared__ float xch[2][kLdsRowThreads / 64 + 1];
+  uint32_t parity = 0;
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x, parity ^= 1u) {
+    const AmRowItem it = am_row_decode<kLdsRowThreads>(AM_TABLE_ARGS, n_items, item);
+    const AmSeg& S = *it.seg;
+    const uint64_t units = S.units_per_block;
+    const uint64_t steps = (units + kLdsRowThreads * kLdsRowUnroll - 1) / (kLdsRowThreads * kLdsRowUnroll);
+    const uint64_t v_idx = S.v_first + it.block;
+    float v_old = 0.0f;
+    if (threadIdx.x == 0) v_old = v[v_idx];
+
+    // pass 1: HBM -> registers -> LDS, sum of squares on the way
+    float ss = 0.0f;
+    for (uint64_t i = 0; i < steps; ++i) {
+      Raw r[kLdsRowUnroll];
+#pragma unroll
+      for (int j = 0; j < kLdsRowUnroll; ++j) {
+        const uint64_t u = am_lds_unit(i, j);
+        if (u < units) r[j] = am_load_grad_raw<G, VEC>(S.g, it.elem0 + u * VEC);
+      }
+#pragma unroll
+      for (int j = 0; j < kLdsRowUnroll; ++j) {
+        const uint64_t u = am_lds_unit(i, j);
+        if (u < units) {
+          stage[u] = r[j];
+          float gv[VEC];
+          am_widen(r[j], gv);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) ss = fmaf(gv[e], gv[e], ss);
+        }
+      }
+    }
+    ss = am_wave_sum(ss);
+    float* slot = xch[parity];
+    if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = ss;
+    if (threadIdx.x == 0) slot[kLdsRowThreads / 64] = v_old;
+    __syncthreads();  // also orders the LDS staging before pass 2 (each thread re-reads only its own units,
+                      // but the barrier is needed for the sums anyway)
+    ss = slot[0];
+#pragma unroll
+    for (int w = 1; w < kLdsRowThreads / 64; ++w) ss += slot[w];
+    v_old = slot[kLdsRowThreads / 64];
+
+    float v_new, scale;
+    am_block_scalars(ss, (float)S.block_numel, v_old, sc, &v_new, &scale);
+    const float decay = sc.lr_wd * S.wd_scale;
+    if (threadIdx.x == 0) v[v_idx] = v_new;
+
+    // pass 2: m and p from HBM, g from LDS
+    for (uint64_t i = 0; i < steps; ++i) {
+      float mv[kLdsRowUnroll][VEC], pv[kLdsRowUnroll][VEC];
+#pragma unroll
+      for (int j = 0; j < kLdsRowUnroll; ++j) {
+        const uint64_t u = am_lds_unit(i, j);
+        if (u < units) {
+          const uint64_t e = it.elem0 + u * VEC;
+          am_load_f32<VEC>(S.m, e, mv[j]);
+          am_load_f32<VEC>(S.p, e, pv[j]);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kLdsRowUnroll; ++j) {
+        const uint64_t u = am_lds_unit(i, j);
+        if (u < units) {
+          float gv[VEC];
+          am_widen(stage[u], gv);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) am_update_elem(gv[e], mv[j][e], pv[j][e], scale, decay, sc);
+          const uint64_t e0 = it.elem0 + u * VEC;
+          am_store_f32<VEC>(S.m, e0, mv[j]);
+          am_store_f32<VEC>(S.p, e0, pv[j]);
+        }
+      }
+    }
+    __syncthreads();  // the next item of a grid-stride pass overwrites the stage
+  }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_ids(AM_TABLE_PARAMS, uint32_t n_items,
+                                                                 uint32_t tensor, uint64_t* __restrict__ ids) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmRowItem it = am_row_decode<kLdsRowThreads>(AM_TABLE_ARGS, n_items, item);
+    const AmSeg& S = *it.seg;
+    if (S.tensor != tensor) continue;
+    const uint64_t units = S.units_per_block;
+    const uint64_t steps = (units + kLdsRowThreads * kLdsRowUnroll - 1) / (kLdsRowThreads * kLdsRowUnroll);
+    const uint64_t v_idx = S.v_first + it.block;
+    for (uint64_t i = 0; i < steps; ++i)
+#pragma unroll
+      for (int j = 0; j < kLdsRowUnroll; ++j) {
+        const uint64_t u = am_lds_unit(i, j);
+        if (u < units) {
+          const uint64_t e = it.elem0 + u * VEC;
+#pragma unroll
+          for (int k = 0; k < VEC; ++k) ids[e + k] = v_idx;
+        }
+      }
   }
 }
 

@@ -172,6 +172,10 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       items = ti.n_blocks * cpb;
       bk.n_lblocks += ti.n_blocks;
     }
+    if (var.family == AM_FAM_ROW_LDS) {
+      const uint64_t bytes = d.block_numel * (grad_dtype == ADAM_MINI_GRAD_BF16 ? 2u : 4u);
+      if (bytes > bk.lds_bytes) bk.lds_bytes = bytes;
+    }
     bk.n_items += items;
     // a launch indexes work items with 32 bits
     if (bk.n_items >= (1ull << 31) || bk.n_lblocks >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;

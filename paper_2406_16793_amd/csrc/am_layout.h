@@ -27,6 +27,7 @@ struct AmBucket {
   uint64_t n_items = 0;     // total work items (ROW: blocks, LARGE: chunks, ELEMENTWISE: tiles)
   uint64_t n_lblocks = 0;   // LARGE: total blocks (length of the scale scratch)
   uint64_t table_offset = 0;  // index of segs[0] in the concatenated device table
+  uint64_t lds_bytes = 0;     // ROW_LDS: bytes of LDS that hold the largest block's gradient
 };
 
 // Knobs of the variant choice (process-wide defaults; copied into a layout when it is built).
@@ -39,7 +40,7 @@ struct AmTuning {
   int64_t max_upt = 4;              // preferred upper bound on units per thread: the smallest team that
                                     //   stays within it is chosen; exceeded only when no team fits otherwise
   int64_t row_max_units = 1 << 30;  // blocks above this never use the single-pass register kernel
-  int64_t lds_max_bytes = 0;        // > 0: blocks that do not fit the register kernel and whose gradient fits
+  int64_t lds_max_bytes = 150 * 1024;       // > 0: blocks that do not fit the register kernel and whose gradient fits
                                     //      in this many bytes of LDS use the LDS-staged single-pass kernel
   int64_t large_chunk_upt = 4;      // LARGE: units per thread of a 256-thread chunk (1, 2, 4, 8 or 16)
   int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (1, 2, 4 or 8)

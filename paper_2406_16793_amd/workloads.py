@@ -116,6 +116,14 @@ def gpt2_small() -> Workload:
                     zero_row_tensors=_embedding_indices(specs))
 
 
+def gpt2_small_bf16() -> Workload:
+    """GPT-2-small shape with bf16 gradients (not a BASELINE configuration): its 64x768 query / key
+    head blocks carry 96 KB of gradient each, the case served by the LDS-staged kernel."""
+    wl = gpt2_small()
+    wl.name, wl.config_id, wl.grad_dtype, wl.rtol = "gpt2_small_bf16", 6, "bf16", 5e-3
+    return wl
+
+
 def llama2_7b() -> Workload:
     """Config 3: 32 layers, d_model 4096, 32 heads (head_dim 128), SwiGLU MLP 11008,
     vocab 32000; fp32 params and m, bf16 grads; 10 steps.  291 tensors,
@@ -141,7 +149,7 @@ def llama2_13b() -> Workload:
     return Workload("llama2_13b", 5, specs, "f32", 5, grad_dist="student_t3")
 
 
-WORKLOADS = {"tiny": tiny, "gpt2_small": gpt2_small, "llama2_7b": llama2_7b,
+WORKLOADS = {"tiny": tiny, "gpt2_small": gpt2_small, "gpt2_small_bf16": gpt2_small_bf16, "llama2_7b": llama2_7b,
              "llama3_8b": llama3_8b, "llama2_13b": llama2_13b}
 
 

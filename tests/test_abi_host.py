@@ -109,8 +109,14 @@ def test_set_option_validation():
         B.adam_mini_set_option("row_max_units", -1)
     B.adam_mini_set_option("row_max_units", 1024)
     h = B.adam_mini_init_layout([(4096 * 8, 4096 * 2, 1.0)], B.GRAD_F32, -1)
+    assert B.adam_mini_export_layout(h)[1] == [B.PATH_ROW_LDS]      # 32 KB of gradient: staged in LDS
+    B.adam_mini_destroy_layout(h)
+    B.adam_mini_set_option("lds_max_bytes", 0)
+    h = B.adam_mini_init_layout([(4096 * 8, 4096 * 2, 1.0)], B.GRAD_F32, -1)
     assert B.adam_mini_export_layout(h)[1] == [B.PATH_LARGE]
     B.adam_mini_destroy_layout(h)
+    with pytest.raises(B.AdamMiniError):
+        B.adam_mini_set_option("lds_max_bytes", 200 * 1024)          # more than a compute unit has
     B.adam_mini_set_option("reset", 0)
     h = B.adam_mini_init_layout([(4096 * 8, 4096 * 2, 1.0)], B.GRAD_F32, -1)
     assert B.adam_mini_export_layout(h)[1] == [B.PATH_ROW]
@@ -137,7 +143,8 @@ def test_layout_matches_oracle_block_index(oracle, dtype):
         for e in probe:
             assert B.adam_mini_block_id(h, k, e) == int(want[e])
     assert kind[2] == B.PATH_ELEMENTWISE and kind[6] == B.PATH_ELEMENTWISE
-    assert kind[4] == B.PATH_ROW and kind[5] == B.PATH_LARGE
+    # 49152-element blocks: 192 KB of fp32 gradient needs the multi-workgroup path, 96 KB of bf16 fits in LDS
+    assert kind[4] == B.PATH_ROW and kind[5] == (B.PATH_LARGE if dtype == B.GRAD_F32 else B.PATH_ROW_LDS)
     B.adam_mini_destroy_layout(h)
 
 

@@ -34,6 +34,34 @@ def test_crafted_layouts(shapes, grad_dtype):
     run.close()
 
 
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_lds_staged_kernel(grad_dtype, oracle):
+    """Blocks too big for the register kernel whose gradient fits in LDS: single pass through LDS."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import binding as B
+    B.adam_mini_set_option("lds_max_bytes", 150 * 1024)
+    try:
+        shapes = [(3, 24580), (2, 32768), (2, 36000), (1, 38400), (5, 4096), (1, 100000), (2, 65536), (1, 76800)]
+        wl = _wl(shapes, grad_dtype, steps=3)
+        run, st, worst = H.run_both(wl, check_every_step=True)
+        kinds = B.adam_mini_export_layout(run.opt.layout)[1]
+        limit = 150 * 1024 // (2 if grad_dtype == "bf16" else 4)
+        for (nb, bn), kind in zip(shapes, kinds):
+            want = B.PATH_ROW if bn <= 24576 else (B.PATH_ROW_LDS if bn <= limit else B.PATH_LARGE)
+            assert kind == want, (bn, kind, want)
+        numel = [s.numel for s in wl.specs]
+        bnum = [s.block_numel for s in wl.specs]
+        for k in range(len(shapes)):
+            got = run.opt.block_ids(k)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), oracle.block_ids_tensor(numel, bnum, k).astype(np.int64))
+        print("lds staged: worst normwise rel err %.3g" % worst, flush=True)
+        run.close()
+    finally:
+        B.adam_mini_set_option("reset", 0)
+
+
 def test_block_ids_device_layout_is_bit_exact(oracle):
     """Every element's v index, as the device tables map it, against the oracle's function."""
     import gpu_harness as H
