@@ -210,8 +210,11 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *   "large_chunk_upt"    units per thread of a chunk in the multi-workgroup path (1, 2, 4, 8, 16)
  *   "ew_upt"             units per thread of a tile in the AdamW-equivalent kernel (1, 2, 4, 8)
  *   "grid_cap"           > 0: cap on workgroups per launch (grid-stride loop beyond it)
- *   "row_wg_per_cu"      > 0: cap on resident row-kernel workgroups per compute unit (bounds the bytes
- *                        in flight; HBM efficiency drops when the chip is oversubscribed), 0 = no cap
+ *   "row_inflight_kb"    row kernel: resident workgroups per compute unit are capped so that the loads
+ *                        they keep in flight stay near this many KB (HBM efficiency drops when the chip
+ *                        is oversubscribed); 0 = no cap
+ *   "row_wg_per_cu"      > 0: fixed cap on resident row-kernel workgroups per compute unit instead
+ *   "row_blocked"        1: each wavefront of a row team owns a contiguous span of the block
  *   "stream_wg_per_cu"   the same cap for the AdamW-equivalent and large-block update kernels
  *   "reset"              restore the defaults (value ignored)
  * Returns ADAM_MINI_INVALID_ARG for an unknown key or a negative value.

@@ -134,6 +134,19 @@ int launch_capped(K kernel, uint32_t grid, uint32_t block, int64_t cap, hipStrea
   return ADAM_MINI_OK;
 }
 
+// Resident-workgroup cap of a row bucket: explicit, or derived from the bytes a workgroup loads.
+int64_t row_cap(const AmBucket& bk, int teams, size_t grad_bytes, const AmTuning& t) {
+  if (t.row_wg_per_cu > 0) return t.row_wg_per_cu;
+  if (t.row_inflight_kb <= 0) return 0;
+  uint64_t units = 0;
+  for (const AmSeg& s : bk.segs)
+    if (s.units_per_block > units) units = s.units_per_block;
+  const uint64_t wg_bytes = units * (uint64_t)bk.var.vec * (8 + grad_bytes) * (uint64_t)teams;
+  int64_t cap = (int64_t)(((uint64_t)t.row_inflight_kb * 1024 + wg_bytes - 1) / (wg_bytes ? wg_bytes : 1));
+  if (cap < 2) cap = 2;
+  return cap > 16 ? 0 : cap;  // beyond 16 the hardware's own limits bind first
+}
+
 template <typename G, int VEC>
 int launch_row(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc,
                const AmTuning& t, hipStream_t stream) {
@@ -143,7 +156,8 @@ int launch_row(const AmVariant& var, const AmBucket& bk, const AmTable& tab, flo
     if (var.lanes == L && var.upt == U) {                                                             \
       constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                               \
       const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                            \
-      return launch_capped(am_row_kernel<G, VEC, L, U>, grid, WG, t.row_wg_per_cu, stream, AM_TAB,    \
+      return launch_capped(am_row_kernel<G, VEC, L, U>, grid, WG, row_cap(bk, TEAMS, sizeof(G), t),   \
+                           stream, AM_TAB,                                                            \
                            n_items, (uint32_t)(t.row_blocked != 0), v, sc);                           \
     }                                                                                                 \
   }
@@ -419,6 +433,7 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "ew_upt") g_tuning.ew_upt = value;
   else if (k == "grid_cap") g_tuning.grid_cap = value;
   else if (k == "row_wg_per_cu") g_tuning.row_wg_per_cu = value;
+  else if (k == "row_inflight_kb") g_tuning.row_inflight_kb = value;
   else if (k == "row_blocked") g_tuning.row_blocked = value;
   else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
   else return ADAM_MINI_INVALID_ARG;

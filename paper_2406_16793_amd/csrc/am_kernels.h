@@ -51,9 +51,19 @@ __device__ __forceinline__ AmRowItem am_row_decode(AM_TABLE_PARAMS, uint32_t n_i
   AmRowItem it;
   it.active = item < n_items;
   if (!it.active) item = n_items - 1;  // keep the lookup in range; loads and stores are masked
-  // a team of whole wavefronts shares its item: keep the table walk on the scalar unit
-  if constexpr (LANES >= 64) item = __builtin_amdgcn_readfirstlane(item);
-  const uint32_t s = am_find_seg(item_keys, n_segs, item);
+  uint32_t s;
+  if constexpr (LANES >= 64) {
+    // a team of whole wavefronts shares its item: keep the table walk on the scalar unit
+    item = __builtin_amdgcn_readfirstlane(item);
+    s = am_find_seg(item_keys, n_segs, item);
+  } else {
+    // several teams per wavefront: walk the table once for the workgroup's first item (scalar);
+    // only teams that fall past that tensor's last item repeat the walk with their own item
+    const uint32_t lead = first_item < n_items ? first_item : n_items - 1;
+    s = am_find_seg(item_keys, n_segs, lead);
+    const uint32_t next_key = s + 1 < n_segs ? item_keys[s + 1] : 0xffffffffu;
+    if (item >= next_key) s = am_find_seg(item_keys, n_segs, item);
+  }
   it.seg = segs + s;
   it.block = item - item_keys[s];
   it.elem0 = (uint64_t)it.block * it.seg->block_numel;

@@ -124,6 +124,42 @@ def gpt2_small_bf16() -> Workload:
     return wl
 
 
+def gpt2_small_whole() -> Workload:
+    """GPT-2-small tensors under the paper's "Partition for non-Transformers" (Appendix B):
+    every tensor is ONE block (38.6 M elements for the embedding), fp32 gradients.  Not a BASELINE
+    configuration; it exercises the multi-workgroup path on whole-tensor blocks."""
+    from .partition import partition_whole
+    wl = gpt2_small()
+    wl.specs = partition_whole([(s.name, s.shape) for s in wl.specs])
+    wl.name, wl.config_id, wl.steps = "gpt2_small_whole", 7, 5
+    return wl
+
+
+def llama2_7b_value_whole() -> Workload:
+    """Llama-2-7B shape with the appendix's value "strategy II": each value matrix is one
+    16.8 M-element block instead of 4096 row blocks.  Not a BASELINE configuration."""
+    specs = partition_transformer(_llama_shapes(32, 4096, 32, 32, 11008, 32000), n_heads=32, value_whole=True)
+    return Workload("llama2_7b_value_whole", 8, specs, "bf16", 5, rtol=5e-3)
+
+
+def llama2_7b_lora() -> Workload:
+    """Rank-128 LoRA adapters on the seven linear maps of every Llama-2-7B layer: 448 small
+    matrices A [128, in] and B [out, 128], partitioned by output neuron (rows of 4096 / 11008 /
+    128 elements), no weight decay, bf16 gradients.  Not a BASELINE configuration; it stresses
+    the multi-tensor packing and launch overhead rather than bandwidth."""
+    r, d, f = 128, 4096, 11008
+    names = []
+    for i in range(32):
+        pre = "layers.%d." % i
+        for nm, (out_f, in_f) in (("attn.query", (d, d)), ("attn.key", (d, d)), ("attn.value", (d, d)),
+                                  ("attn.proj", (d, d)), ("mlp.gate", (f, d)), ("mlp.up", (f, d)),
+                                  ("mlp.down", (d, f))):
+            names.append((pre + nm + ".lora_A.mlp", (r, in_f)))     # "mlp" keyword: split by output neuron
+            names.append((pre + nm + ".lora_B.mlp", (out_f, r)))
+    specs = [TensorSpec(n, tuple(sh), sh[1], 0.0) for n, sh in names]
+    return Workload("llama2_7b_lora", 9, specs, "bf16", 5, weight_decay=0.0, rtol=5e-3)
+
+
 def llama2_7b() -> Workload:
     """Config 3: 32 layers, d_model 4096, 32 heads (head_dim 128), SwiGLU MLP 11008,
     vocab 32000; fp32 params and m, bf16 grads; 10 steps.  291 tensors,
@@ -149,7 +185,9 @@ def llama2_13b() -> Workload:
     return Workload("llama2_13b", 5, specs, "f32", 5, grad_dist="student_t3")
 
 
-WORKLOADS = {"tiny": tiny, "gpt2_small": gpt2_small, "gpt2_small_bf16": gpt2_small_bf16, "llama2_7b": llama2_7b,
+WORKLOADS = {"tiny": tiny, "gpt2_small": gpt2_small, "gpt2_small_bf16": gpt2_small_bf16,
+             "gpt2_small_whole": gpt2_small_whole, "llama2_7b_value_whole": llama2_7b_value_whole,
+             "llama2_7b_lora": llama2_7b_lora, "llama2_7b": llama2_7b,
              "llama3_8b": llama3_8b, "llama2_13b": llama2_13b}
 
 

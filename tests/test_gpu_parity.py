@@ -210,3 +210,15 @@ def test_misaligned_pointer_is_rejected_on_the_gpu_too():
     torch.cuda.synchronize()
     assert torch.equal(before, run.p[0])          # nothing was launched
     run.close()
+
+
+@pytest.mark.parametrize("name", ["gpt2_small_whole", "llama2_7b_lora"])
+def test_other_partitions_and_shapes(name):
+    """Whole-tensor blocks ("Partition for non-Transformers") and a LoRA-shaped list of 448 small
+    matrices, complete sets, every element compared."""
+    import gpu_harness as H
+    from paper_2406_16793_amd import workloads
+    wl = workloads.get(name)
+    run, st, worst = H.run_both(wl, steps=3, gen_device="cuda")
+    print("%s: worst normwise rel err %.3g" % (name, worst), flush=True)
+    run.close()
