@@ -50,12 +50,12 @@ class OracleLib:
         lib = ctypes.CDLL(path)
         u64, dbl, vp = ctypes.c_uint64, ctypes.c_double, ctypes.c_void_p
         lib.amo_step_tensor.restype = ctypes.c_int
-        lib.amo_step_tensor.argtypes = [vp, vp, vp, vp, ctypes.c_int, u64, u64,
+        lib.amo_step_tensor.argtypes = [vp, vp, vp, vp, ctypes.c_int, u64, u64, ctypes.c_int,
                                         dbl, dbl, dbl, dbl, dbl, u64]
         lib.amo_block_id.restype = u64
-        lib.amo_block_id.argtypes = [vp, vp, ctypes.c_uint32, ctypes.c_uint32, u64]
+        lib.amo_block_id.argtypes = [vp, vp, vp, ctypes.c_uint32, ctypes.c_uint32, u64]
         lib.amo_block_ids_tensor.restype = ctypes.c_int
-        lib.amo_block_ids_tensor.argtypes = [vp, vp, ctypes.c_uint32, ctypes.c_uint32, vp]
+        lib.amo_block_ids_tensor.argtypes = [vp, vp, vp, ctypes.c_uint32, ctypes.c_uint32, vp]
         lib.amo_num_blocks.restype = u64
         lib.amo_num_blocks.argtypes = [vp, vp, ctypes.c_uint32]
         lib.amo_num_threads.restype = ctypes.c_int
@@ -66,10 +66,12 @@ class OracleLib:
         return int(self._lib.amo_num_threads())
 
     def step_tensor(self, p: np.ndarray, m: np.ndarray, v: np.ndarray, g: np.ndarray,
-                    block_numel: int, hp: "Hyper", t: int, wd_scale: float = 1.0) -> None:
+                    block_numel: int, hp: "Hyper", t: int, wd_scale: float = 1.0,
+                    strided: bool = False) -> None:
         """One step on one tensor, in place.  p, m: float64[numel]; v:
         float64[numel // block_numel]; g: float32 / float64 / uint16 (bf16 bits).
-        The decay coefficient of the tensor is weight_decay * wd_scale."""
+        The decay coefficient of the tensor is weight_decay * wd_scale.
+        strided: the blocks are the columns of the row-major [block_numel, n_blocks] tensor."""
         numel = p.size
         for a in (p, m, v):
             if a.dtype != np.float64 or not a.flags.c_contiguous:
@@ -81,26 +83,39 @@ class OracleLib:
         lam = hp.weight_decay * float(np.float32(wd_scale))
         rc = self._lib.amo_step_tensor(p.ctypes.data, m.ctypes.data, v.ctypes.data,
                                        g.ctypes.data, _grad_dtype_code(g), numel,
-                                       block_numel, hp.lr, hp.beta1, hp.beta2, hp.eps,
-                                       lam, t)
+                                       block_numel, 1 if strided else 0, hp.lr, hp.beta1, hp.beta2,
+                                       hp.eps, lam, t)
         if rc != 0:
             raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
 
-    def block_id(self, numel: Sequence[int], block_numel: Sequence[int], tensor: int, elem: int) -> int:
+    @staticmethod
+    def _strided_arg(strided, n):
+        if strided is None:
+            return None, None
+        a = np.ascontiguousarray([1 if x else 0 for x in strided], dtype=np.int32)
+        if a.size != n:
+            raise ValueError("strided must have one entry per tensor")
+        return a, a.ctypes.data
+
+    def block_id(self, numel: Sequence[int], block_numel: Sequence[int], tensor: int, elem: int,
+                 strided: Optional[Sequence[bool]] = None) -> int:
         """v index used by element `elem` of tensor `tensor`."""
         n = np.ascontiguousarray(numel, dtype=np.uint64)
         b = np.ascontiguousarray(block_numel, dtype=np.uint64)
-        r = self._lib.amo_block_id(n.ctypes.data, b.ctypes.data, len(n), tensor, elem)
+        keep, sp = self._strided_arg(strided, len(n))
+        r = self._lib.amo_block_id(n.ctypes.data, b.ctypes.data, sp, len(n), tensor, elem)
         if r == 2 ** 64 - 1:
             raise IndexError("tensor/element out of range")
         return int(r)
 
-    def block_ids_tensor(self, numel: Sequence[int], block_numel: Sequence[int], tensor: int) -> np.ndarray:
+    def block_ids_tensor(self, numel: Sequence[int], block_numel: Sequence[int], tensor: int,
+                         strided: Optional[Sequence[bool]] = None) -> np.ndarray:
         """v index of every element of tensor `tensor` (uint64 array)."""
         n = np.ascontiguousarray(numel, dtype=np.uint64)
         b = np.ascontiguousarray(block_numel, dtype=np.uint64)
+        keep, sp = self._strided_arg(strided, len(n))
         out = np.empty(int(n[tensor]), dtype=np.uint64)
-        if self._lib.amo_block_ids_tensor(n.ctypes.data, b.ctypes.data, len(n), tensor, out.ctypes.data) != 0:
+        if self._lib.amo_block_ids_tensor(n.ctypes.data, b.ctypes.data, sp, len(n), tensor, out.ctypes.data) != 0:
             raise IndexError("tensor out of range")
         return out
 
@@ -150,20 +165,20 @@ def _grad_dtype_code(g: np.ndarray) -> int:
     raise TypeError("gradient must be float32, float64 or uint16 (bf16 bits), got %s" % g.dtype)
 
 
-def step_tensor(p, m, v, g, block_numel, hp, t, wd_scale=1.0) -> None:
-    default_lib().step_tensor(p, m, v, g, block_numel, hp, t, wd_scale)
+def step_tensor(p, m, v, g, block_numel, hp, t, wd_scale=1.0, strided=False) -> None:
+    default_lib().step_tensor(p, m, v, g, block_numel, hp, t, wd_scale, strided)
 
 
-def block_id(numel, block_numel, tensor, elem) -> int:
-    return default_lib().block_id(numel, block_numel, tensor, elem)
+def block_id(numel, block_numel, tensor, elem, strided=None) -> int:
+    return default_lib().block_id(numel, block_numel, tensor, elem, strided)
 
 
 def num_blocks(numel, block_numel) -> int:
     return default_lib().num_blocks(numel, block_numel)
 
 
-def block_ids_tensor(numel, block_numel, tensor) -> np.ndarray:
-    return default_lib().block_ids_tensor(numel, block_numel, tensor)
+def block_ids_tensor(numel, block_numel, tensor, strided=None) -> np.ndarray:
+    return default_lib().block_ids_tensor(numel, block_numel, tensor, strided)
 
 
 class OracleState:
@@ -176,8 +191,9 @@ class OracleState:
 
     def __init__(self, numel: Sequence[int], block_numel: Sequence[int],
                  wd_scale: Optional[Sequence[float]], params0: Sequence[np.ndarray],
-                 lib: Optional[OracleLib] = None):
+                 lib: Optional[OracleLib] = None, strided: Optional[Sequence[bool]] = None):
         self.lib = lib or default_lib()
+        self.strided = [False] * len(numel) if strided is None else [bool(x) for x in strided]
         self.numel = [int(x) for x in numel]
         self.block_numel = [int(x) for x in block_numel]
         self.wd_scale = [1.0] * len(self.numel) if wd_scale is None else [float(x) for x in wd_scale]
@@ -194,7 +210,7 @@ class OracleState:
         self.t += 1
         for k, g in enumerate(grads):
             self.lib.step_tensor(self.p[k], self.m[k], self.v[k], np.ascontiguousarray(g).reshape(-1),
-                                 self.block_numel[k], hp, self.t, self.wd_scale[k])
+                                 self.block_numel[k], hp, self.t, self.wd_scale[k], self.strided[k])
 
     def v_flat(self) -> np.ndarray:
         return np.concatenate(self.v) if self.v else np.zeros(0)

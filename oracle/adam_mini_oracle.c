@@ -22,7 +22,9 @@
  * The blocks of one tensor are the consecutive, equally sized, contiguous runs
  * of `block_numel` elements of the row-major tensor: that is what "partition
  * by tokens / heads / output neurons" (Algorithm 3, Appendix B) yields when the
- * partition dimension is the outermost one.  block_numel == 1 is vanilla AdamW
+ * partition dimension is the outermost one.  When a codebase stores the weight
+ * transposed (Appendix D notes that re-ordering is then needed) the same blocks
+ * are the COLUMNS of the stored matrix: the `strided` form below.  block_numel == 1 is vanilla AdamW
  * (Section 2.3, "replaces g.*g in vanilla Adam by its mean value"); block_numel
  * == numel is the non-Transformer partition (Algorithm "Partition for
  * non-Transformers", Appendix B).
@@ -57,30 +59,34 @@ static double amo_grad_at(const void *g, int dtype, uint64_t i) {
 
 /*
  * One step of Algorithm 1 on ONE block of n elements.
- *   p, m : n doubles, updated in place;  v : the block's scalar, in place
- *   g, dtype, g_first : gradient buffer, its element type, index of the
- *                       block's first element inside it
+ *   p, m : the block's first element; element i of the block is p[i * stride]
+ *          (stride 1: a contiguous run; stride > 1: a column of a row-major matrix)
+ *   v    : the block's scalar, in place
+ *   g, dtype, g_first : gradient buffer, its element type, index of the block's
+ *                       first element inside it (element i is g_first + i * stride)
  *   t >= 1 : step counter used by the bias corrections
  */
 void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
-                    uint64_t g_first, uint64_t n, double lr, double beta1,
-                    double beta2, double eps, double lambda, uint64_t t) {
+                    uint64_t g_first, uint64_t n, uint64_t stride, double lr,
+                    double beta1, double beta2, double eps, double lambda,
+                    uint64_t t) {
   double bias1 = 1.0 - pow(beta1, (double)t);
   double bias2 = 1.0 - pow(beta2, (double)t);
 
   /* param = param - lr * lambda * param */
-  for (uint64_t i = 0; i < n; ++i) p[i] = p[i] - lr * lambda * p[i];
+  for (uint64_t i = 0; i < n; ++i)
+    p[i * stride] = p[i * stride] - lr * lambda * p[i * stride];
 
   /* m = (1 - beta1) * g + beta1 * m */
   for (uint64_t i = 0; i < n; ++i) {
-    double gi = amo_grad_at(g, dtype, g_first + i);
-    m[i] = (1.0 - beta1) * gi + beta1 * m[i];
+    double gi = amo_grad_at(g, dtype, g_first + i * stride);
+    m[i * stride] = (1.0 - beta1) * gi + beta1 * m[i * stride];
   }
 
   /* v = (1 - beta2) * mean(g .* g) + beta2 * v : one scalar for the block */
   double sum_sq = 0.0;
   for (uint64_t i = 0; i < n; ++i) {
-    double gi = amo_grad_at(g, dtype, g_first + i);
+    double gi = amo_grad_at(g, dtype, g_first + i * stride);
     sum_sq += gi * gi;
   }
   double mean_sq = sum_sq / (double)n;
@@ -91,19 +97,25 @@ void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
 
   /* param = param - lr * m_hat / (sqrt(v_hat) + eps), m_hat = m / (1 - beta1^t) */
   for (uint64_t i = 0; i < n; ++i) {
-    double m_hat = m[i] / bias1;
-    p[i] = p[i] - lr * m_hat / (sqrt(v_hat) + eps);
+    double m_hat = m[i * stride] / bias1;
+    p[i * stride] = p[i * stride] - lr * m_hat / (sqrt(v_hat) + eps);
   }
 }
 
 /*
- * One step on one tensor of `numel` elements cut into numel/block_numel
- * consecutive blocks.  v points at this tensor's first scalar (one per block).
- * Blocks never interact, so they are handed to the host threads as they come.
+ * One step on one tensor of `numel` elements cut into numel/block_numel blocks.
+ * strided == 0: block b is the contiguous run [b*block_numel, (b+1)*block_numel).
+ * strided != 0: the tensor is a row-major [block_numel, n_blocks] matrix and
+ *               block b is its COLUMN b (elements r*n_blocks + b): the layout a
+ *               weight takes when a codebase stores W as its transpose, the case
+ *               for which the paper's appendix says re-ordering is needed
+ *               (Appendix D, last paragraph on Hessian plots).
+ * v points at this tensor's first scalar (one per block).  Blocks never
+ * interact, so they are handed to the host threads as they come.
  * Returns 0, or -1 when the descriptor is not a valid uniform partition.
  */
 int amo_step_tensor(double *p, double *m, double *v, const void *g, int dtype,
-                    uint64_t numel, uint64_t block_numel, double lr,
+                    uint64_t numel, uint64_t block_numel, int strided, double lr,
                     double beta1, double beta2, double eps, double lambda,
                     uint64_t t) {
   if (numel == 0 || block_numel == 0 || numel % block_numel != 0 || t == 0)
@@ -111,9 +123,10 @@ int amo_step_tensor(double *p, double *m, double *v, const void *g, int dtype,
   int64_t n_blocks = (int64_t)(numel / block_numel);
 #pragma omp parallel for schedule(static)
   for (int64_t b = 0; b < n_blocks; ++b) {
-    uint64_t first = (uint64_t)b * block_numel;
+    uint64_t first = strided ? (uint64_t)b : (uint64_t)b * block_numel;
+    uint64_t stride = strided ? (uint64_t)n_blocks : 1;
     amo_step_block(p + first, m + first, v + b, g, dtype, first, block_numel,
-                   lr, beta1, beta2, eps, lambda, t);
+                   stride, lr, beta1, beta2, eps, lambda, t);
   }
   return 0;
 }
@@ -122,23 +135,28 @@ int amo_step_tensor(double *p, double *m, double *v, const void *g, int dtype,
  * Index of the second-moment scalar that element `elem` of tensor `tensor`
  * uses, when the v scalars of all tensors are stored back to back in tensor
  * order.  Written as a running count of blocks, independent of any table.
+ * strided may be NULL (all tensors contiguous).
  * Returns UINT64_MAX on a bad argument.
  */
 uint64_t amo_block_id(const uint64_t *numel, const uint64_t *block_numel,
-                      uint32_t n_tensors, uint32_t tensor, uint64_t elem) {
+                      const int32_t *strided, uint32_t n_tensors,
+                      uint32_t tensor, uint64_t elem) {
   if (tensor >= n_tensors || elem >= numel[tensor]) return UINT64_MAX;
   uint64_t blocks_before = 0;
   for (uint32_t k = 0; k < tensor; ++k)
     blocks_before += numel[k] / block_numel[k];
+  if (strided && strided[tensor])
+    return blocks_before + elem % (numel[tensor] / block_numel[tensor]);
   return blocks_before + elem / block_numel[tensor];
 }
 
 /* amo_block_id for every element of one tensor: out[e], e = 0 .. numel[tensor]-1. */
 int amo_block_ids_tensor(const uint64_t *numel, const uint64_t *block_numel,
-                         uint32_t n_tensors, uint32_t tensor, uint64_t *out) {
+                         const int32_t *strided, uint32_t n_tensors,
+                         uint32_t tensor, uint64_t *out) {
   if (tensor >= n_tensors) return -1;
   for (uint64_t e = 0; e < numel[tensor]; ++e)
-    out[e] = amo_block_id(numel, block_numel, n_tensors, tensor, e);
+    out[e] = amo_block_id(numel, block_numel, strided, n_tensors, tensor, e);
   return 0;
 }
 

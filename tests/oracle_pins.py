@@ -376,6 +376,54 @@ def pin_layout_invariants(lib):
                 raise AssertionError("block %d has %d elements, want %d" % (first + j, seen[first + j], bnum[k]))
 
 
+# ---------------------------------------------------------------------------
+# P9: strided (column) blocks.  A weight stored as its transpose has the same blocks, now as
+# the columns of the stored matrix (Appendix D: "some extra re-ordering is needed").  The
+# strided form must give, bit for bit, the transpose of what the contiguous form gives on
+# the re-ordered data, and must agree with a brute-force loop over param[:, j].
+# ---------------------------------------------------------------------------
+def pin_strided_blocks(lib):
+    rng = np.random.default_rng(41)
+    B, n = 7, 5                                   # 7 blocks of 5 elements
+    hp = orc.Hyper(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    W0 = rng.normal(0, 1, (B, n))                 # logical layout: block = row
+    pc, mc, vc = W0.ravel().copy(), np.zeros(B * n), np.zeros(B)
+    ps, ms, vs = W0.T.ravel().copy(), np.zeros(B * n), np.zeros(B)     # stored transposed: [n, B]
+    P = W0.T.copy()
+    M = np.zeros((n, B))
+    V = [0.0] * B
+    for t in range(1, 4):
+        G = rng.normal(0, 0.1, (B, n))
+        lib.step_tensor(pc, mc, vc, G.ravel().copy(), n, hp, t)
+        lib.step_tensor(ps, ms, vs, G.T.ravel().copy(), n, hp, t, strided=True)
+        if not (np.array_equal(ps.reshape(n, B).T.ravel(), pc) and np.array_equal(ms.reshape(n, B).T.ravel(), mc)
+                and np.array_equal(vs, vc)):
+            raise AssertionError("strided result is not the transpose of the contiguous result (t=%d)" % t)
+        GT = G.T
+        for j in range(B):                        # brute force over param[:, j], Python floats
+            g = GT[:, j].tolist()
+            pv = [x - hp.lr * hp.weight_decay * x for x in P[:, j].tolist()]
+            mv = [(1 - hp.beta1) * gi + hp.beta1 * mi for gi, mi in zip(g, M[:, j].tolist())]
+            V[j] = (1 - hp.beta2) * (sum(gi * gi for gi in g) / n) + hp.beta2 * V[j]
+            vhat = V[j] / (1 - hp.beta2 ** t)
+            pv = [x - hp.lr * (mi / (1 - hp.beta1 ** t)) / (math.sqrt(vhat) + hp.eps) for x, mi in zip(pv, mv)]
+            P[:, j] = pv
+            M[:, j] = mv
+        _close(ps, P.ravel(), 1e-12, 1e-15, "strided brute-force param t=%d" % t)
+        _close(ms, M.ravel(), 1e-12, 1e-15, "strided brute-force m t=%d" % t)
+        _close(vs, V, 1e-12, 0, "strided brute-force v t=%d" % t)
+    # block ids: element (r, j) of the stored [n, B] matrix belongs to block j
+    numel, bnum, strided = [6, B * n, 4], [3, n, 1], [False, True, False]
+    want = 2 + np.tile(np.arange(B), n)
+    for e in range(B * n):
+        if lib.block_id(numel, bnum, 1, e, strided) != int(want[e]):
+            raise AssertionError("strided block_id(%d)" % e)
+    if lib.block_id(numel, bnum, 2, 0, strided) != 2 + B:
+        raise AssertionError("blocks after a strided tensor")
+    if not np.array_equal(lib.block_ids_tensor(numel, bnum, 1, strided), want.astype(np.uint64)):
+        raise AssertionError("strided block_ids_tensor")
+
+
 ALL_PINS = [pin_hand_worked, pin_adamw_reduction, pin_constant_gradient,
             pin_ema_and_five_param_example, pin_bruteforce_partition, pin_symmetries,
-            pin_first_step, pin_grad_dtypes, pin_layout_invariants]
+            pin_first_step, pin_grad_dtypes, pin_layout_invariants, pin_strided_blocks]

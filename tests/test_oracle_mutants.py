@@ -8,16 +8,16 @@ import oracle_pins
 
 # (label, text in oracle/adam_mini_oracle.c, replacement)
 MUTANTS = [
-    ("no weight decay", "p[i] = p[i] - lr * lambda * p[i];", "p[i] = p[i];"),
-    ("decay uses gradient scale (sign flipped)", "p[i] = p[i] - lr * lambda * p[i];", "p[i] = p[i] + lr * lambda * p[i];"),
-    ("beta1 weights swapped", "m[i] = (1.0 - beta1) * gi + beta1 * m[i];", "m[i] = beta1 * gi + (1.0 - beta1) * m[i];"),
-    ("m uses beta2", "m[i] = (1.0 - beta1) * gi + beta1 * m[i];", "m[i] = (1.0 - beta2) * gi + beta2 * m[i];"),
+    ("no weight decay", "p[i * stride] = p[i * stride] - lr * lambda * p[i * stride];", "p[i * stride] = p[i * stride];"),
+    ("decay sign flipped", "p[i * stride] = p[i * stride] - lr * lambda * p[i * stride];", "p[i * stride] = p[i * stride] + lr * lambda * p[i * stride];"),
+    ("beta1 weights swapped", "m[i * stride] = (1.0 - beta1) * gi + beta1 * m[i * stride];", "m[i * stride] = beta1 * gi + (1.0 - beta1) * m[i * stride];"),
+    ("m uses beta2", "m[i * stride] = (1.0 - beta1) * gi + beta1 * m[i * stride];", "m[i * stride] = (1.0 - beta2) * gi + beta2 * m[i * stride];"),
     ("sum instead of mean", "double mean_sq = sum_sq / (double)n;", "double mean_sq = sum_sq;"),
     ("mean of |g| instead of g*g", "sum_sq += gi * gi;", "sum_sq += fabs(gi);"),
     ("square of the mean", "double mean_sq = sum_sq / (double)n;", "double mean_sq = sum_sq / (double)n; mean_sq = mean_sq * mean_sq;"),
     ("beta2 weights swapped", "*v = (1.0 - beta2) * mean_sq + beta2 * (*v);", "*v = beta2 * mean_sq + (1.0 - beta2) * (*v);"),
     ("v not accumulated", "*v = (1.0 - beta2) * mean_sq + beta2 * (*v);", "*v = (1.0 - beta2) * mean_sq;"),
-    ("no bias correction of m", "double m_hat = m[i] / bias1;", "double m_hat = m[i];"),
+    ("no bias correction of m", "double m_hat = m[i * stride] / bias1;", "double m_hat = m[i * stride];"),
     ("no bias correction of v", "double v_hat = *v / bias2;", "double v_hat = *v;"),
     ("bias correction of m uses t+1", "double bias1 = 1.0 - pow(beta1, (double)t);", "double bias1 = 1.0 - pow(beta1, (double)t + 1.0);"),
     ("bias correction of v uses t+1", "double bias2 = 1.0 - pow(beta2, (double)t);", "double bias2 = 1.0 - pow(beta2, (double)t + 1.0);"),
@@ -26,13 +26,19 @@ MUTANTS = [
     ("eps dropped", "(sqrt(v_hat) + eps)", "(sqrt(v_hat))"),
     ("eps added twice", "(sqrt(v_hat) + eps)", "(sqrt(v_hat) + eps + eps)"),
     ("no square root", "(sqrt(v_hat) + eps)", "(v_hat + eps)"),
-    ("update sign", "p[i] = p[i] - lr * m_hat / (sqrt(v_hat) + eps);", "p[i] = p[i] + lr * m_hat / (sqrt(v_hat) + eps);"),
-    ("update uses g not m", "double m_hat = m[i] / bias1;", "double m_hat = amo_grad_at(g, dtype, g_first + i);"),
-    ("gradient offset ignored", "amo_step_block(p + first, m + first, v + b, g, dtype, first,", "amo_step_block(p + first, m + first, v + b, g, dtype, 0,"),
+    ("update sign", "p[i * stride] = p[i * stride] - lr * m_hat / (sqrt(v_hat) + eps);", "p[i * stride] = p[i * stride] + lr * m_hat / (sqrt(v_hat) + eps);"),
+    ("update uses g not m", "double m_hat = m[i * stride] / bias1;", "double m_hat = amo_grad_at(g, dtype, g_first + i * stride);"),
+    ("gradient offset ignored", "amo_step_block(p + first, m + first, v + b, g, dtype, first, block_numel,", "amo_step_block(p + first, m + first, v + b, g, dtype, 0, block_numel,"),
     ("one v for the whole tensor", "amo_step_block(p + first, m + first, v + b,", "amo_step_block(p + first, m + first, v + 0 * b,"),
     ("block id ignores earlier tensors", "return blocks_before + elem / block_numel[tensor];", "return elem / block_numel[tensor];"),
     ("block id counts elements", "blocks_before += numel[k] / block_numel[k];", "blocks_before += numel[k];"),
     ("block id rounds up", "return blocks_before + elem / block_numel[tensor];", "return blocks_before + (elem + block_numel[tensor] - 1) / block_numel[tensor];"),
+    ("strided blocks: gradient read with stride 1", "double gi = amo_grad_at(g, dtype, g_first + i * stride);\n    sum_sq", "double gi = amo_grad_at(g, dtype, g_first + i);\n    sum_sq"),
+    ("strided blocks: first element b*block_numel", "uint64_t first = strided ? (uint64_t)b : (uint64_t)b * block_numel;", "uint64_t first = (uint64_t)b * block_numel;"),
+    ("strided blocks: stride is block_numel", "uint64_t stride = strided ? (uint64_t)n_blocks : 1;", "uint64_t stride = strided ? block_numel : 1;"),
+    ("strided blocks: flag ignored", "uint64_t stride = strided ? (uint64_t)n_blocks : 1;", "uint64_t stride = 1;"),
+    ("strided block id uses division", "return blocks_before + elem % (numel[tensor] / block_numel[tensor]);", "return blocks_before + elem / block_numel[tensor];"),
+    ("strided block id modulo block_numel", "return blocks_before + elem % (numel[tensor] / block_numel[tensor]);", "return blocks_before + elem % block_numel[tensor];"),
     ("bf16 shifted wrongly", "<< 16;", "<< 15;"),
 ]
 
