@@ -58,13 +58,24 @@ enum {
   ADAM_MINI_PATH_ELEMENTWISE = 0, /* block_numel == 1: AdamW-equivalent, dense v */
   ADAM_MINI_PATH_ROW = 1,         /* whole block held in registers of <= one workgroup; single pass */
   ADAM_MINI_PATH_LARGE = 2,       /* block spans several workgroups: partial sums, finalize, update */
-  ADAM_MINI_PATH_ROW_LDS = 3      /* whole block staged in one workgroup's LDS; single pass */
+  ADAM_MINI_PATH_ROW_LDS = 3,     /* whole block staged in one workgroup's LDS; single pass */
+  ADAM_MINI_PATH_STRIDED = 4      /* blocks are columns of the stored matrix: column partial sums, finalize, update */
+};
+
+/* adam_mini_tensor_desc.flags */
+enum {
+  /* The tensor is stored as a row-major [block_numel, numel/block_numel] matrix and block j is its
+   * COLUMN j (elements r*n_blocks + j): the layout of a weight whose codebase keeps W as its
+   * transpose, for which the paper's Appendix D says the blocks must be re-ordered.  Results equal
+   * those of the contiguous form on the transposed data. */
+  ADAM_MINI_FLAG_STRIDED = 1u
 };
 
 /*
  * One tensor of the multi-tensor list.  The tensor is contiguous, row-major, with
  * the partition dimension outermost; its blocks are elements
- * [j*block_numel, (j+1)*block_numel), j = 0 .. numel/block_numel - 1.
+ * [j*block_numel, (j+1)*block_numel), j = 0 .. numel/block_numel - 1
+ * (with ADAM_MINI_FLAG_STRIDED the partition dimension is innermost instead, see the flag).
  *   rows of an [out,in] weight (value / attn.proj / mlp; embed / output by token): block_numel = in
  *   heads of a [heads*head_dim, in] query / key weight:                            block_numel = head_dim*in
  *   any other tensor (norm gains, biases):                                          block_numel = numel
@@ -74,7 +85,7 @@ typedef struct adam_mini_tensor_desc {
   uint64_t numel;       /* > 0 */
   uint64_t block_numel; /* > 0 and divides numel */
   float wd_scale;       /* lambda_k = weight_decay * wd_scale (1 for decayed tensors, 0 for none); finite, >= 0 */
-  uint32_t flags;       /* reserved, must be 0 */
+  uint32_t flags;       /* 0 or ADAM_MINI_FLAG_STRIDED; other bits are reserved and must be 0 */
 } adam_mini_tensor_desc;
 
 /* Hyper-parameters of one step (Algorithm 1, lines 1 and 5-10). */
@@ -216,6 +227,7 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *   "row_wg_per_cu"      > 0: fixed cap on resident row-kernel workgroups per compute unit instead
  *   "row_blocked"        1: each wavefront of a row team owns a contiguous span of the block
  *   "stream_wg_per_cu"   the same cap for the AdamW-equivalent and large-block update kernels
+ *   "strided_wg_per_cu"  the same cap for the column-block (ADAM_MINI_FLAG_STRIDED) update kernel
  *   "reset"              restore the defaults (value ignored)
  * Returns ADAM_MINI_INVALID_ARG for an unknown key or a negative value.
  */

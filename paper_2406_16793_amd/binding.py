@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(HERE, "libadam_mini.so")
 
 OK, INVALID_ARG, MISALIGNED, OUT_OF_MEMORY, HIP_ERROR, NO_DEVICE = 0, -1, -2, -3, -4, -5
 GRAD_F32, GRAD_BF16 = 0, 1
-PATH_ELEMENTWISE, PATH_ROW, PATH_LARGE, PATH_ROW_LDS = 0, 1, 2, 3
+PATH_ELEMENTWISE, PATH_ROW, PATH_LARGE, PATH_ROW_LDS, PATH_STRIDED = 0, 1, 2, 3, 4
+FLAG_STRIDED = 1
 
 
 class TensorDesc(ctypes.Structure):
@@ -210,7 +211,9 @@ class AdamMini:
         self.specs = list(specs)
         self.grad_dtype = GRAD_BF16 if grad_dtype == "bf16" else GRAD_F32
         self.device = device
-        self.layout = adam_mini_init_layout([(s.numel, s.block_numel, s.wd_scale) for s in self.specs],
+        self.layout = adam_mini_init_layout([(s.numel, s.block_numel, s.wd_scale,
+                                              FLAG_STRIDED if getattr(s, "strided", False) else 0)
+                                             for s in self.specs],
                                             self.grad_dtype, device)
         self.num_blocks = adam_mini_num_blocks(self.layout)
         self._ptrs = None

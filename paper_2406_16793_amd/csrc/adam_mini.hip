@@ -212,6 +212,31 @@ int launch_row_lds_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, 
 }
 
 template <typename G, int VEC>
+int launch_strided(const AmBucket& bk, const AmTable& tab, float* v, float* partials, float* scales,
+                   const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t n_cols = (uint32_t)bk.n_lblocks;
+  const uint32_t grid = grid_for(bk.n_items, t);
+  const uint32_t fgrid = grid_for((bk.n_lblocks + 255) / 256, t);
+  hipLaunchKernelGGL((am_strided_partial<G, VEC>), dim3(grid), dim3(kStridedThreads), 0, stream, AM_TAB, n_items,
+                     partials);
+  hipLaunchKernelGGL(am_strided_finalize, dim3(fgrid), dim3(256), 0, stream, AM_TAB, n_cols,
+                     (const float*)partials, v, scales, sc);
+  return launch_capped(am_strided_update<G, VEC>, grid, kStridedThreads, t.strided_wg_per_cu, stream, AM_TAB,
+                       n_items, (const float*)scales, sc);
+}
+
+template <int VEC>
+int launch_strided_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmTuning& t,
+                       hipStream_t stream) {
+  const uint32_t n_items = (uint32_t)bk.n_items;
+  const uint32_t grid = grid_for(bk.n_items, t);
+  hipLaunchKernelGGL((am_strided_ids<VEC>), dim3(grid), dim3(kStridedThreads), 0, stream, AM_TAB, n_items, tensor,
+                     ids);
+  return ADAM_MINI_OK;
+}
+
+template <typename G, int VEC>
 int launch_large(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v, float* partials,
                  float* scales, const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
   const uint32_t n_items = (uint32_t)bk.n_items;
@@ -327,6 +352,8 @@ int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, 
         return launch_row<typename T::G, T::VEC>(var, bk, tab, v, sc, t, stream);
       case AM_FAM_ROW_LDS:
         return launch_row_lds<typename T::G, T::VEC>(bk, tab, v, sc, t, stream);
+      case AM_FAM_STRIDED:
+        return launch_strided<typename T::G, T::VEC>(bk, tab, v, L->partials_dev, L->scales_dev, sc, t, stream);
       case AM_FAM_LARGE:
         return launch_large<typename T::G, T::VEC>(var, bk, tab, v, L->partials_dev, L->scales_dev, sc, t, stream);
       case AM_FAM_ELEMENTWISE:
@@ -349,6 +376,8 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
         return launch_row_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
       case AM_FAM_ROW_LDS:
         return launch_row_lds_ids<VEC>(bk, tab, tensor, ids, t, stream);
+      case AM_FAM_STRIDED:
+        return launch_strided_ids<VEC>(bk, tab, tensor, ids, t, stream);
       case AM_FAM_LARGE:
         return launch_large_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
       case AM_FAM_ELEMENTWISE:
@@ -436,6 +465,7 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "row_inflight_kb") g_tuning.row_inflight_kb = value;
   else if (k == "row_blocked") g_tuning.row_blocked = value;
   else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
+  else if (k == "strided_wg_per_cu") g_tuning.strided_wg_per_cu = value;
   else return ADAM_MINI_INVALID_ARG;
   return ADAM_MINI_OK;
 }
@@ -495,7 +525,7 @@ int adam_mini_block_id(const adam_mini_layout* layout, uint32_t tensor, uint64_t
   if (!layout || !out || tensor >= layout->host.tensors.size()) return ADAM_MINI_INVALID_ARG;
   const AmTensorInfo& ti = layout->host.tensors[tensor];
   if (elem >= ti.numel) return ADAM_MINI_INVALID_ARG;
-  *out = ti.v_first + elem / ti.block_numel;
+  *out = ti.strided ? ti.v_first + elem % ti.n_blocks : ti.v_first + elem / ti.block_numel;
   return ADAM_MINI_OK;
 }
 
@@ -646,7 +676,7 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
     o.lanes = bk.var.lanes;
     o.upt = bk.var.upt;
     o.n_tensors = (uint32_t)bk.segs.size();
-    o.n_kernels = bk.var.family == AM_FAM_LARGE ? 3u : 1u;
+    o.n_kernels = (bk.var.family == AM_FAM_LARGE || bk.var.family == AM_FAM_STRIDED) ? 3u : 1u;
     o.n_items = bk.n_items;
     for (const AmSeg& s : bk.segs) {
       const AmTensorInfo& ti = layout->host.tensors[s.tensor];
@@ -660,7 +690,9 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
     const char* kname = bk.var.family == AM_FAM_ROW ? "am_row_kernel"
                         : bk.var.family == AM_FAM_LARGE ? "am_large_update"
                         : bk.var.family == AM_FAM_ROW_LDS ? "am_row_lds_kernel" : "am_elementwise";
-    if (bk.var.family == AM_FAM_ROW_LDS)
+    if (bk.var.family == AM_FAM_STRIDED)
+      std::snprintf(o.kernel, sizeof o.kernel, "am_strided_update<%s, %d>", gname, bk.var.vec);
+    else if (bk.var.family == AM_FAM_ROW_LDS)
       std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d>", kname, gname, bk.var.vec);
     else
       std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d, %d, %d>", kname, gname, bk.var.vec, bk.var.lanes, bk.var.upt);

@@ -8,6 +8,7 @@
 //   am_large_partial     blocks too big for one workgroup: per-chunk sum(g^2)
 //   am_large_finalize    per block: fixed-order sum of its chunk partials, v update, step scale
 //   am_large_update      per chunk: m and p update with the block's step scale
+//   am_strided_*         blocks that are the columns of the stored matrix (weight kept transposed)
 //   am_elementwise       block_numel == 1 (AdamW-equivalent): dense v, per-element sqrt / divide
 //   am_*_ids             the same work-item -> element walks, writing v indices instead
 //
@@ -437,6 +438,159 @@ __global__ __launch_bounds__(THREADS) void am_large_ids(AM_TABLE_PARAMS,
         const uint64_t e = it.elem0 + u * VEC;
 #pragma unroll
         for (int j = 0; j < VEC; ++j) ids[e + j] = v_idx;
+      }
+    }
+  }
+}
+
+// ===========================================================================
+// STRIDED family: the tensor is a row-major [R, C] matrix whose blocks are its C columns
+// (a weight stored transposed).  A lane owns VEC adjacent columns, a workgroup 256*VEC of them,
+// and a work item is one chunk of kStridedRows rows of that column group: every access is still a
+// contiguous 128-bit run along a row, and column sums need no cross-lane reduction at all.
+//   am_strided_partial   per item: sum of g^2 of each owned column over the row chunk
+//   am_strided_finalize  per column: fixed-order sum over the row chunks (double), v update, step scale
+//   am_strided_update    per item: m and p update with the per-column step scales
+// ===========================================================================
+constexpr int kStridedThreads = 256;
+constexpr int kStridedRows = 16;   // rows per work item
+constexpr int kStridedUnroll = 4;  // rows in flight per thread
+
+struct AmStridedItem {
+  const AmSeg* seg;
+  uint64_t row0;       // first row of the chunk
+  uint64_t unit;       // unit index inside a row owned by this lane
+  uint32_t row_chunk;
+  bool lane_on;        // the lane's unit exists
+};
+
+__device__ __forceinline__ AmStridedItem am_strided_decode(AM_TABLE_PARAMS, uint32_t item) {
+  const uint32_t s = am_find_seg(item_keys, n_segs, item);
+  AmStridedItem it;
+  it.seg = segs + s;
+  const uint32_t local = item - item_keys[s];
+  it.row_chunk = local / it.seg->chunks_per_block;
+  const uint32_t group = local - it.row_chunk * it.seg->chunks_per_block;
+  it.row0 = (uint64_t)it.row_chunk * kStridedRows;
+  it.unit = (uint64_t)group * kStridedThreads + threadIdx.x;
+  it.lane_on = it.unit < it.seg->units_per_block;
+  return it;
+}
+
+template <typename G, int VEC>
+__global__ __launch_bounds__(kStridedThreads) void am_strided_partial(AM_TABLE_PARAMS, uint32_t n_items,
+                                                                      float* __restrict__ partials) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
+    const AmSeg& S = *it.seg;
+    const uint64_t rows = S.block_numel, row_len = S.row_len;
+    float acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
+    for (int r = 0; r < kStridedRows; r += kStridedUnroll) {
+      float gv[kStridedUnroll][VEC];
+#pragma unroll
+      for (int q = 0; q < kStridedUnroll; ++q) {
+        const uint64_t row = it.row0 + r + q;
+        if (it.lane_on && row < rows) {
+          am_load_grad<G, VEC>(S.g, row * row_len + it.unit * VEC, gv[q]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) gv[q][j] = 0.0f;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kStridedUnroll; ++q)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = fmaf(gv[q][j], gv[q][j], acc[j]);
+    }
+    // plain (cached) stores: the finalize kernel reads these back right away
+    if (it.lane_on) {
+      float* dst = partials + S.aux + (uint64_t)it.row_chunk * row_len + it.unit * VEC;
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) dst[j] = acc[j];
+    }
+  }
+}
+
+// One thread per column of the bucket.
+__global__ __launch_bounds__(256) void am_strided_finalize(AM_TABLE_PARAMS, uint32_t n_cols,
+                                                           const float* __restrict__ partials,
+                                                           float* __restrict__ v, float* __restrict__ scales,
+                                                           AmScalars sc) {
+  for (uint32_t gc = blockIdx.x * 256 + threadIdx.x; gc < n_cols; gc += gridDim.x * 256) {
+    const uint32_t s = am_find_seg(lblock_keys, n_segs, gc);
+    const AmSeg& S = segs[s];
+    const uint64_t col = gc - lblock_keys[s];
+    const uint64_t rows = S.block_numel, row_len = S.row_len;
+    const uint64_t n_chunks = (rows + kStridedRows - 1) / kStridedRows;
+    double acc = 0.0;
+    for (uint64_t c = 0; c < n_chunks; ++c) acc += (double)partials[S.aux + c * row_len + col];
+    const uint64_t v_idx = S.v_first + col;
+    float v_new, scale;
+    am_block_scalars((float)acc, (float)rows, v[v_idx], sc, &v_new, &scale);
+    v[v_idx] = v_new;
+    scales[gc] = scale;
+  }
+}
+
+template <typename G, int VEC>
+__global__ __launch_bounds__(kStridedThreads) void am_strided_update(AM_TABLE_PARAMS, uint32_t n_items,
+                                                                     const float* __restrict__ scales,
+                                                                     AmScalars sc) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
+    const AmSeg& S = *it.seg;
+    const uint64_t rows = S.block_numel, row_len = S.row_len;
+    const float decay = sc.lr_wd * S.wd_scale;
+    float scale[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) scale[j] = 0.0f;
+    if (it.lane_on) {
+      const float* src = scales + S.lblock_first + it.unit * VEC;
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) scale[j] = src[j];
+    }
+    for (int r = 0; r < kStridedRows; r += kStridedUnroll) {
+      float gv[kStridedUnroll][VEC], mv[kStridedUnroll][VEC], pv[kStridedUnroll][VEC];
+#pragma unroll
+      for (int q = 0; q < kStridedUnroll; ++q) {
+        const uint64_t row = it.row0 + r + q;
+        if (it.lane_on && row < rows) {
+          const uint64_t e = row * row_len + it.unit * VEC;
+          am_load_grad<G, VEC>(S.g, e, gv[q]);
+          am_load_f32<VEC>(S.m, e, mv[q]);
+          am_load_f32<VEC>(S.p, e, pv[q]);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kStridedUnroll; ++q) {
+        const uint64_t row = it.row0 + r + q;
+        if (it.lane_on && row < rows) {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) am_update_elem(gv[q][j], mv[q][j], pv[q][j], scale[j], decay, sc);
+          const uint64_t e = row * row_len + it.unit * VEC;
+          am_store_f32<VEC>(S.m, e, mv[q]);
+          am_store_f32<VEC>(S.p, e, pv[q]);
+        }
+      }
+    }
+  }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kStridedThreads) void am_strided_ids(AM_TABLE_PARAMS, uint32_t n_items,
+                                                                  uint32_t tensor, uint64_t* __restrict__ ids) {
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
+    const AmSeg& S = *it.seg;
+    if (S.tensor != tensor || !it.lane_on) continue;
+    for (int r = 0; r < kStridedRows; ++r) {
+      const uint64_t row = it.row0 + r;
+      if (row < S.block_numel) {
+        const uint64_t e = row * S.row_len + it.unit * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) ids[e + j] = S.v_first + it.unit * VEC + j;
       }
     }
   }

@@ -57,6 +57,7 @@ int am_path_kind(const AmVariant& v) {
     case AM_FAM_ELEMENTWISE: return ADAM_MINI_PATH_ELEMENTWISE;
     case AM_FAM_ROW: return ADAM_MINI_PATH_ROW;
     case AM_FAM_ROW_LDS: return ADAM_MINI_PATH_ROW_LDS;
+    case AM_FAM_STRIDED: return ADAM_MINI_PATH_STRIDED;
     default: return ADAM_MINI_PATH_LARGE;
   }
 }
@@ -122,7 +123,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
   for (uint32_t k = 0; k < n_tensors; ++k) {
     const adam_mini_tensor_desc& d = descs[k];
     if (d.numel == 0 || d.block_numel == 0 || d.numel % d.block_numel != 0) return ADAM_MINI_INVALID_ARG;
-    if (d.flags != 0) return ADAM_MINI_INVALID_ARG;
+    if ((d.flags & ~(uint32_t)ADAM_MINI_FLAG_STRIDED) != 0) return ADAM_MINI_INVALID_ARG;
     if (!std::isfinite(d.wd_scale) || d.wd_scale < 0.0f) return ADAM_MINI_INVALID_ARG;
     if (d.numel >= (1ull << 48)) return ADAM_MINI_INVALID_ARG;  // keeps every product below in 64 bits
     AmTensorInfo ti{};
@@ -133,7 +134,20 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     ti.v_first = v_next;
     v_next += ti.n_blocks;
 
-    const AmVariant var = am_choose_variant(grad_dtype, d.numel, d.block_numel, ti.v_first, tuning);
+    // Column blocks of a [block_numel, n_blocks] matrix.  With one column the block is the whole
+    // (contiguous) tensor and with one row every element is its own block: both are plain layouts.
+    ti.strided = (d.flags & ADAM_MINI_FLAG_STRIDED) != 0 && ti.n_blocks > 1 && d.block_numel > 1;
+    AmVariant var;
+    if (ti.strided) {
+      const int native = grad_dtype == ADAM_MINI_GRAD_BF16 ? (tuning.bf16_vec == 8 ? 8 : 4) : 4;
+      var.family = AM_FAM_STRIDED;
+      // a row must be a whole number of units, and the tensor's v slice 16-byte aligned for the scale loads
+      var.vec = (ti.n_blocks % (uint64_t)native == 0) ? native : 1;
+      var.lanes = 256;
+      var.upt = 16;
+    } else {
+      var = am_choose_variant(grad_dtype, d.numel, d.block_numel, ti.v_first, tuning);
+    }
     int b = -1;
     for (size_t i = 0; i < out->buckets.size(); ++i)
       if (same_variant(out->buckets[i].var, var)) b = (int)i;
@@ -161,6 +175,18 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       s.block_numel = d.numel;
       s.units_per_block = (d.numel + (uint64_t)var.vec - 1) / (uint64_t)var.vec;
       items = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
+    } else if (var.family == AM_FAM_STRIDED) {
+      const uint64_t rows = d.block_numel, cols = ti.n_blocks;
+      s.row_len = cols;
+      s.units_per_block = cols / (uint64_t)var.vec;                        // units per stored row
+      const uint64_t groups = (s.units_per_block + 255) / 256;             // column groups of 256 units
+      const uint64_t row_chunks = (rows + 15) / 16;                        // 16 rows per work item
+      if (groups >= (1ull << 31) || cols >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
+      s.chunks_per_block = (uint32_t)groups;
+      s.aux = bk.n_partials;                                               // partial sums: [row_chunks][cols]
+      bk.n_partials += row_chunks * cols;
+      bk.n_lblocks += cols;                                                // one step scale per column
+      items = row_chunks * groups;
     } else if (var.family == AM_FAM_ROW || var.family == AM_FAM_ROW_LDS) {
       s.units_per_block = d.block_numel / (uint64_t)var.vec;
       items = ti.n_blocks;
@@ -193,6 +219,9 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     out->n_segs += bk.segs.size();
     if (bk.var.family == AM_FAM_LARGE) {
       if (bk.n_items > out->n_partials) out->n_partials = bk.n_items;
+      if (bk.n_lblocks > out->n_lblocks) out->n_lblocks = bk.n_lblocks;
+    } else if (bk.var.family == AM_FAM_STRIDED) {
+      if (bk.n_partials > out->n_partials) out->n_partials = bk.n_partials;
       if (bk.n_lblocks > out->n_lblocks) out->n_lblocks = bk.n_lblocks;
     }
   }

@@ -17,6 +17,7 @@ struct AmTensorInfo {
   float wd_scale;
   uint64_t v_first;   // exclusive prefix sum of numel / block_numel
   uint64_t n_blocks;
+  bool strided;       // blocks are the columns of the stored [block_numel, n_blocks] matrix
   int bucket;         // index into AmHostLayout::buckets
   int seg;            // index into that bucket's segs
 };
@@ -25,7 +26,8 @@ struct AmBucket {
   AmVariant var;
   std::vector<AmSeg> segs;  // pointers left null here; filled at step time
   uint64_t n_items = 0;     // total work items (ROW: blocks, LARGE: chunks, ELEMENTWISE: tiles)
-  uint64_t n_lblocks = 0;   // LARGE: total blocks (length of the scale scratch)
+  uint64_t n_lblocks = 0;   // LARGE: total blocks, STRIDED: total columns (length of the scale scratch)
+  uint64_t n_partials = 0;  // STRIDED: floats of partial sums the bucket needs
   uint64_t table_offset = 0;  // index of segs[0] in the concatenated device table
   uint64_t lds_bytes = 0;     // ROW_LDS: bytes of LDS that hold the largest block's gradient
 };
@@ -49,6 +51,7 @@ struct AmTuning {
                                     //   loads they keep in flight stay near this many KB (0 = no cap)
   int64_t row_wg_per_cu = 0;        // > 0: fixed cap on resident row-kernel workgroups per compute unit (overrides row_inflight_kb)
   int64_t row_blocked = 0;          // 1: each wavefront of a row team owns a contiguous span of the block
+  int64_t strided_wg_per_cu = 4;    // > 0: cap on resident workgroups per compute unit of the column-block update kernel
   int64_t stream_wg_per_cu = 2;     // > 0: same for the elementwise / large-update streaming kernels
 };
 

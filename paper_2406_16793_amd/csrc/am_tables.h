@@ -14,7 +14,8 @@ enum AmFamily : int {
   AM_FAM_ELEMENTWISE = 0,  // block_numel == 1; item = tile of units of one tensor
   AM_FAM_ROW = 1,          // item = one block, held in the registers of a team of LANES threads
   AM_FAM_LARGE = 2,        // item = one chunk of a block; partial sums + finalize + update
-  AM_FAM_ROW_LDS = 3       // item = one block, gradient staged in the workgroup's LDS
+  AM_FAM_ROW_LDS = 3,      // item = one block, gradient staged in the workgroup's LDS
+  AM_FAM_STRIDED = 4       // blocks are columns: item = (row chunk, group of 256 column units)
 };
 
 // One tensor inside one bucket.  Device pointers are filled in at step time.
@@ -31,7 +32,12 @@ struct AmSeg {
   uint32_t tensor;        // index in the caller's tensor list
   float wd_scale;         // lambda_k = weight_decay * wd_scale
   uint32_t pad_;
+  uint64_t aux;           // STRIDED: index of the tensor's first partial sum in the scratch
+  uint64_t row_len;       // STRIDED: elements per stored row (= number of blocks C)
 };
+// STRIDED reuses the fields as: block_numel = rows R of the stored [R, C] matrix (elements per block),
+// units_per_block = units per ROW (C / VEC), chunks_per_block = column groups per row chunk,
+// lblock_first = number of columns of the bucket before this tensor (index into the scale scratch).
 
 // A bucket's device tables.  The two key arrays repeat item_first / lblock_first of every
 // segment densely, so the binary search of a workgroup stays inside a few cache lines.

@@ -30,6 +30,7 @@ class TensorSpec:
     shape: Tuple[int, ...]
     block_numel: int
     wd_scale: float = 1.0
+    strided: bool = False   # blocks are the COLUMNS of the stored [block_numel, n_blocks] matrix (weight kept transposed)
 
     @property
     def numel(self) -> int:
@@ -116,3 +117,12 @@ def partition_whole(named_shapes: Sequence[Tuple[str, Sequence[int]]], decay_1d:
 def as_adamw(specs: Sequence[TensorSpec]) -> List[TensorSpec]:
     """The AdamW-equivalent mode: same tensors, every block of size 1."""
     return [TensorSpec(s.name, s.shape, 1, s.wd_scale) for s in specs]
+
+
+def transposed(spec: TensorSpec) -> TensorSpec:
+    """The same 2-D weight and the same blocks, stored as the transpose: a [rows, cols] tensor cut
+    by rows becomes a [cols, rows] tensor whose blocks are its columns (the re-ordering case of the
+    paper's Appendix D).  Only for tensors partitioned by their outermost dimension's rows."""
+    if len(spec.shape) != 2 or spec.strided or spec.block_numel != spec.shape[1]:
+        raise ValueError("transposed() needs a 2-D tensor partitioned by rows")
+    return TensorSpec(spec.name + ".T", (spec.shape[1], spec.shape[0]), spec.block_numel, spec.wd_scale, True)

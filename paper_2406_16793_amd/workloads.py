@@ -160,6 +160,18 @@ def llama2_7b_lora() -> Workload:
     return Workload("llama2_7b_lora", 9, specs, "bf16", 5, weight_decay=0.0, rtol=5e-3)
 
 
+def llama2_7b_embed_t() -> Workload:
+    """Llama-2-7B shape whose embedding and output matrices are stored transposed ([4096, 32000]),
+    so their per-token blocks are the columns of the stored matrix (the re-ordering case of the
+    paper's Appendix D).  Not a BASELINE configuration."""
+    from .partition import transposed
+    wl = llama2_7b()
+    wl.specs = [transposed(s) if (s.name.startswith("embed") or s.name.startswith("output")) else s
+                for s in wl.specs]
+    wl.name, wl.config_id, wl.steps = "llama2_7b_embed_t", 10, 5
+    return wl
+
+
 def llama2_7b() -> Workload:
     """Config 3: 32 layers, d_model 4096, 32 heads (head_dim 128), SwiGLU MLP 11008,
     vocab 32000; fp32 params and m, bf16 grads; 10 steps.  291 tensors,
@@ -187,7 +199,7 @@ def llama2_13b() -> Workload:
 
 WORKLOADS = {"tiny": tiny, "gpt2_small": gpt2_small, "gpt2_small_bf16": gpt2_small_bf16,
              "gpt2_small_whole": gpt2_small_whole, "llama2_7b_value_whole": llama2_7b_value_whole,
-             "llama2_7b_lora": llama2_7b_lora, "llama2_7b": llama2_7b,
+             "llama2_7b_lora": llama2_7b_lora, "llama2_7b_embed_t": llama2_7b_embed_t, "llama2_7b": llama2_7b,
              "llama3_8b": llama3_8b, "llama2_13b": llama2_13b}
 
 

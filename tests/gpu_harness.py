@@ -37,12 +37,16 @@ def assert_state_close(name, got, want, rtol, is_v=False):
     return float(np.linalg.norm(d) / denom) if denom > 0 else 0.0
 
 
-def make_specs(blocks):
-    """blocks: list of (n_blocks, block_numel[, wd_scale]) -> TensorSpec list."""
+def make_specs(blocks, strided=False):
+    """blocks: list of (n_blocks, block_numel[, wd_scale]) -> TensorSpec list.  strided: the tensors
+    are stored [block_numel, n_blocks] and their blocks are the columns."""
     out = []
     for i, b in enumerate(blocks):
         wd = b[2] if len(b) > 2 else 1.0
-        out.append(TensorSpec("t%d" % i, (b[0], b[1]), b[1], wd))
+        if strided:
+            out.append(TensorSpec("t%d" % i, (b[1], b[0]), b[1], wd, True))
+        else:
+            out.append(TensorSpec("t%d" % i, (b[0], b[1]), b[1], wd))
     return out
 
 
@@ -60,7 +64,7 @@ def run_both(wl: workloads.Workload, steps=None, hp=None, mutate_grad=None, chec
         run.p[k].copy_(x)
         p0.append(x.cpu().numpy())
     st = orc.OracleState([s.numel for s in wl.specs], [s.block_numel for s in wl.specs],
-                         [s.wd_scale for s in wl.specs], p0)
+                         [s.wd_scale for s in wl.specs], p0, strided=[s.strided for s in wl.specs])
     hp = hp or dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
     ohp = orc.Hyper.from_f32(**hp)
     worst = 0.0
@@ -123,7 +127,11 @@ def run_sampled(wl: workloads.Workload, steps=None, per_tensor=6, large_per_tens
     dev_picks = [torch.from_numpy(ix).to(run.dev) for ix in picks]
 
     def gather(tensors, k):
+        # sampled blocks as contiguous rows; for column blocks that is the transposed selection, which
+        # the oracle may then treat as contiguous blocks (its strided form is pinned to equal exactly that)
         s = wl.specs[k]
+        if s.strided:
+            return tensors[k].view(s.block_numel, s.n_blocks)[:, dev_picks[k]].t().contiguous()
         return tensors[k].view(s.n_blocks, s.block_numel)[dev_picks[k]].contiguous()
 
     p0 = []

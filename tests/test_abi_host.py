@@ -56,7 +56,8 @@ def test_init_layout_validation():
     assert _init_rc([(16, 0, 1.0)]) == B.INVALID_ARG                # block_numel = 0
     assert _init_rc([(16, 5, 1.0)]) == B.INVALID_ARG                # does not divide
     assert _init_rc([(16, 32, 1.0)]) == B.INVALID_ARG               # block larger than tensor
-    assert _init_rc([(16, 4, 1.0, 1)]) == B.INVALID_ARG             # flags
+    assert _init_rc([(16, 4, 1.0, 2)]) == B.INVALID_ARG             # reserved flag bits
+    assert _init_rc([(16, 4, 1.0, B.FLAG_STRIDED)]) == 0
     assert _init_rc([(16, 4, float("nan"))]) == B.INVALID_ARG
     assert _init_rc([(16, 4, -1.0)]) == B.INVALID_ARG
     assert _init_rc([(16, 4, 1.0)], dtype=7) == B.INVALID_ARG
@@ -167,4 +168,24 @@ def test_layout_of_benchmark_configs(oracle, name):
             assert kd in (B.PATH_LARGE, B.PATH_ROW_LDS) or s.block_numel <= 16384 * 2
         else:
             assert kd == B.PATH_ROW or "wpe" in s.name
+    B.adam_mini_destroy_layout(h)
+
+
+@pytest.mark.parametrize("dtype", [B.GRAD_F32, B.GRAD_BF16])
+def test_strided_layout_matches_oracle_block_index(oracle, dtype):
+    """Column blocks (ADAM_MINI_FLAG_STRIDED): v numbering against the oracle, bit for bit."""
+    descs = [(12, 4, 1.0, 0), (35, 5, 1.0, 1), (64 * 48, 64, 1.0, 1), (30, 1, 1.0, 0), (9, 9, 0.0, 1), (8, 1, 1.0, 1)]
+    numel = [d[0] for d in descs]
+    bnum = [d[1] for d in descs]
+    strided = [bool(d[3]) for d in descs]
+    h = B.adam_mini_init_layout(descs, dtype, -1)
+    assert B.adam_mini_num_blocks(h) == oracle.num_blocks(numel, bnum)
+    voff, kind = B.adam_mini_export_layout(h)
+    for k in range(len(descs)):
+        want = oracle.block_ids_tensor(numel, bnum, k, strided)
+        for e in range(numel[k]):
+            assert B.adam_mini_block_id(h, k, e) == int(want[e]), (k, e)
+    assert kind[1] == B.PATH_STRIDED and kind[2] == B.PATH_STRIDED
+    assert kind[4] == B.PATH_ROW             # one column: the block is the whole contiguous tensor
+    assert kind[5] == B.PATH_ELEMENTWISE     # one row: every element its own block
     B.adam_mini_destroy_layout(h)

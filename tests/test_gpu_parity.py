@@ -222,3 +222,30 @@ def test_other_partitions_and_shapes(name):
     run, st, worst = H.run_both(wl, steps=3, gen_device="cuda")
     print("%s: worst normwise rel err %.3g" % (name, worst), flush=True)
     run.close()
+
+
+# (n_blocks = columns C, block_numel = rows R) of tensors stored [R, C] whose blocks are the columns
+STRIDED_SHAPES = [(1024, 64), (1000, 33), (1001, 17), (4096, 128), (260, 3), (2, 5000), (8, 8), (12000, 100), (1028, 1)]
+
+
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_strided_column_blocks(grad_dtype, oracle):
+    """Weights stored transposed: blocks are columns (Appendix D's re-ordering case)."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import workloads
+    specs = H.make_specs(STRIDED_SHAPES, strided=True) + H.make_specs([(6, 4096), (2, 49152), (9, 1)])
+    rtol = 5e-3 if grad_dtype == "bf16" else 1e-5
+    wl = workloads.Workload("strided", 91, specs, grad_dtype, 4, rtol=rtol)
+    run, st, worst = H.run_both(wl, check_every_step=True)
+    print("strided: worst normwise rel err %.3g" % worst, flush=True)
+    assert worst < 1e-5
+    numel = [s.numel for s in specs]
+    bnum = [s.block_numel for s in specs]
+    strided = [s.strided for s in specs]
+    for k in range(len(specs)):
+        got = run.opt.block_ids(k)
+        torch.cuda.synchronize()
+        want = oracle.block_ids_tensor(numel, bnum, k, strided).astype(np.int64)
+        assert np.array_equal(got.cpu().numpy(), want), "tensor %d %s" % (k, specs[k].shape)
+    run.close()
