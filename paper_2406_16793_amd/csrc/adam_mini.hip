@@ -243,10 +243,11 @@ int launch_large(const AmVariant& var, const AmBucket& bk, const AmTable& tab, f
   const uint32_t n_lblocks = (uint32_t)bk.n_lblocks;
   const uint32_t grid = grid_for(bk.n_items, t);
   const uint32_t fgrid = grid_for((bk.n_lblocks + 3) / 4, t);
+  const uint32_t pgrid = grid_for((bk.n_items + 3) / 4, t);
 #define X(L, U)                                                                                        \
   if (var.lanes == L && var.upt == U) {                                                                \
-    hipLaunchKernelGGL((am_large_partial<G, VEC, L, U>), dim3(grid), dim3(L), 0, stream, AM_TAB, n_items, \
-                       partials);                                                                      \
+    hipLaunchKernelGGL((am_large_partial<G, VEC, L, U>), dim3(pgrid), dim3(256), 0, stream, AM_TAB,     \
+                       n_items, partials);                                                             \
     hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, AM_TAB, n_lblocks,           \
                        (const float*)partials, v, scales, sc);                                         \
     return launch_capped(am_large_update<G, VEC, L, U>, grid, L, t.stream_wg_per_cu, stream, AM_TAB,   \

@@ -333,19 +333,26 @@ __device__ __forceinline__ uint64_t am_chunk_unit(uint64_t unit0, int k) {
   return unit0 + threadIdx.x + (uint64_t)k * THREADS;
 }
 
+// Sum of g^2 of one chunk per WAVEFRONT (four chunks per 256-thread workgroup): a wavefront walks its
+// chunk of THREADS*UPT units 64 at a time, so there is no LDS traffic and no barrier, and a
+// workgroup reads four times the bytes of one update-kernel item.
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_large_partial(AM_TABLE_PARAMS,
-                                                            uint32_t n_items, float* __restrict__ partials) {
-  __shared__ float slots[2][THREADS / 64];
-  uint32_t parity = 0;
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x, parity ^= 1u) {
+__global__ __launch_bounds__(256) void am_large_partial(AM_TABLE_PARAMS,
+                                                        uint32_t n_items, float* __restrict__ partials) {
+  constexpr int STEPS = THREADS * UPT / 64;  // units per lane
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (uint32_t first = blockIdx.x * 4; first < n_items; first += gridDim.x * 4) {
+    uint32_t item = first + wave;
+    const bool active = item < n_items;
+    if (!active) item = n_items - 1;
+    item = __builtin_amdgcn_readfirstlane(item);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
-    float gv[UPT][VEC];
+    float gv[STEPS][VEC];
 #pragma unroll
-    for (int k = 0; k < UPT; ++k) {
-      const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
-      if (u < S.units_per_block) {
+    for (int k = 0; k < STEPS; ++k) {
+      const uint64_t u = it.unit0 + (uint64_t)k * 64 + lane;
+      if (active && u < S.units_per_block) {
         am_load_grad<G, VEC>(S.g, it.elem0 + u * VEC, gv[k]);
       } else {
 #pragma unroll
@@ -354,11 +361,11 @@ __global__ __launch_bounds__(THREADS) void am_large_partial(AM_TABLE_PARAMS,
     }
     float ss = 0.0f;
 #pragma unroll
-    for (int k = 0; k < UPT; ++k)
+    for (int k = 0; k < STEPS; ++k)
 #pragma unroll
       for (int j = 0; j < VEC; ++j) ss = fmaf(gv[k][j], gv[k][j], ss);
-    ss = am_group_sum<THREADS / 64>(ss, slots[parity]);
-    if (threadIdx.x == 0) partials[item] = ss;
+    ss = am_wave_sum(ss);
+    if (active && lane == 0) partials[item] = ss;
   }
 }
 
