@@ -142,8 +142,9 @@ int64_t row_cap(const AmBucket& bk, int teams, size_t grad_bytes, const AmTuning
   for (const AmSeg& s : bk.segs)
     if (s.units_per_block > units) units = s.units_per_block;
   const uint64_t wg_bytes = units * (uint64_t)bk.var.vec * (8 + grad_bytes) * (uint64_t)teams;
+  if (wg_bytes <= 24 * 1024) return 0;  // small workgroups: the wave-slot limit of a CU is cap enough
   int64_t cap = (int64_t)(((uint64_t)t.row_inflight_kb * 1024 + wg_bytes - 1) / (wg_bytes ? wg_bytes : 1));
-  if (cap < 2) cap = 2;
+  if (cap < 3) cap = 3;
   return cap > 16 ? 0 : cap;  // beyond 16 the hardware's own limits bind first
 }
 

@@ -21,7 +21,8 @@ def assert_state_close(name, got, want, rtol, is_v=False):
     ok = np.isfinite(want)
     assert np.array_equal(np.isfinite(got), ok), "%s: non-finite pattern differs" % name
     w = np.where(ok, want, 0.0)
-    d = np.where(ok, got - want, 0.0)
+    with np.errstate(invalid="ignore"):
+        d = np.where(ok, got - want, 0.0)
     if is_v:
         tol = rtol * np.abs(w) + 1e-30
     else:
