@@ -160,6 +160,9 @@ int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor,
  * any call whose three pointer lists differ from the previous call's, creates or
  * re-uploads the device work tables and waits for that upload.  Results are
  * bitwise reproducible: no atomics on floating-point data, fixed summation order.
+ * A call that neither creates nor re-uploads tables enqueues kernels only (no memset, no
+ * copy), so it may be captured into a HIP graph; the captured step replays with the
+ * hyper-parameters and pointers it was captured with.
  * Concurrent calls on the same layout race on its scratch; use one layout per
  * stream.  Non-finite gradients are not skipped: they propagate into the block's
  * v and parameters (and no other block's).

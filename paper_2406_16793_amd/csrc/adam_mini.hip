@@ -59,8 +59,8 @@ struct adam_mini_layout {
   AmSeg* segs_dev = nullptr;       // all buckets' segments, concatenated
   AmSeg* segs_staging = nullptr;   // pinned host copy
   uint32_t* keys_dev = nullptr;    // [2 * n_segs]: item_first of every segment, then lblock_first
-  float* partials_dev = nullptr;   // LARGE: one float per chunk
-  float* scales_dev = nullptr;     // LARGE: one float per large block
+  float* partials_dev = nullptr;   // LARGE: one float per chunk; STRIDED: [row chunks][columns] per tensor
+  float* scales_dev = nullptr;     // LARGE: one step scale per large block; STRIDED: one per column
   bool tables_valid = false;       // segs_dev holds the pointers below
   std::vector<const void*> cached_p, cached_g, cached_m;
   // optional per-bucket timing: events[(step * n_buckets + bucket) * 2 + {0,1}]
@@ -101,15 +101,19 @@ size_t lds_for_cap(int64_t cap) {
   return kLdsPerCu / (size_t)cap - 1024;  // 1 KiB slack for the kernel's own static LDS
 }
 
+// Kernels launched with more than 64 KB of dynamic LDS need the attribute raised once per device.
 template <typename K>
 int allow_big_lds(K kernel) {
-  static thread_local const void* done[256];
+  struct Done { const void* kernel; int device; };
+  static thread_local Done done[512];
   static thread_local int n_done = 0;
   const void* key = (const void*)kernel;
+  int device = 0;
+  AM_HIP(hipGetDevice(&device));
   for (int i = 0; i < n_done; ++i)
-    if (done[i] == key) return ADAM_MINI_OK;
+    if (done[i].kernel == key && done[i].device == device) return ADAM_MINI_OK;
   AM_HIP(hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsPerCu - 1024)));
-  if (n_done < 256) done[n_done++] = key;
+  if (n_done < 512) done[n_done++] = Done{key, device};
   return ADAM_MINI_OK;
 }
 
@@ -393,8 +397,22 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
 // ---------------------------------------------------------------------------
 // device tables
 // ---------------------------------------------------------------------------
-int ensure_device_state(adam_mini_layout* L) {
-  if (L->device_ready) return ADAM_MINI_OK;
+void free_device_state(adam_mini_layout* L) {
+  if (L->segs_dev) (void)hipFree(L->segs_dev);
+  if (L->segs_staging) (void)hipHostFree(L->segs_staging);
+  if (L->keys_dev) (void)hipFree(L->keys_dev);
+  if (L->partials_dev) (void)hipFree(L->partials_dev);
+  if (L->scales_dev) (void)hipFree(L->scales_dev);
+  L->segs_dev = nullptr;
+  L->segs_staging = nullptr;
+  L->keys_dev = nullptr;
+  L->partials_dev = nullptr;
+  L->scales_dev = nullptr;
+  L->device_ready = false;
+  L->tables_valid = false;
+}
+
+int allocate_device_state(adam_mini_layout* L) {
   const size_t n = L->host.n_segs;
   AM_HIP(hipMalloc((void**)&L->segs_dev, n * sizeof(AmSeg)));
   AM_HIP(hipHostMalloc((void**)&L->segs_staging, n * sizeof(AmSeg), hipHostMallocDefault));
@@ -411,6 +429,22 @@ int ensure_device_state(adam_mini_layout* L) {
       keys[n + bk.table_offset + i] = bk.segs[i].lblock_first;
     }
   AM_HIP(hipMemcpy(L->keys_dev, keys.data(), keys.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+  return ADAM_MINI_OK;
+}
+
+// Device tables and scratch, created by the first call that needs them.  On failure nothing is kept.
+int ensure_device_state(adam_mini_layout* L) {
+  if (L->device_ready) return ADAM_MINI_OK;
+  int rc;
+  try {
+    rc = allocate_device_state(L);
+  } catch (const std::bad_alloc&) {
+    rc = ADAM_MINI_OUT_OF_MEMORY;
+  }
+  if (rc != ADAM_MINI_OK) {
+    free_device_state(L);
+    return rc;
+  }
   L->device_ready = true;
   return ADAM_MINI_OK;
 }
@@ -711,11 +745,7 @@ void adam_mini_destroy_layout(adam_mini_layout* layout) {
   if (layout->device_ready) {
     DeviceGuard guard;
     if (guard.enter(layout->device) == ADAM_MINI_OK) {
-      (void)hipFree(layout->segs_dev);
-      if (layout->keys_dev) (void)hipFree(layout->keys_dev);
-      (void)hipHostFree(layout->segs_staging);
-      if (layout->partials_dev) (void)hipFree(layout->partials_dev);
-      if (layout->scales_dev) (void)hipFree(layout->scales_dev);
+      free_device_state(layout);
     }
   }
   if (!layout->events.empty()) {

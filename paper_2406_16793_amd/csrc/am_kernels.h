@@ -12,9 +12,10 @@
 //   am_elementwise       block_numel == 1 (AdamW-equivalent): dense v, per-element sqrt / divide
 //   am_*_ids             the same work-item -> element walks, writing v indices instead
 //
-// All bulk traffic is 128-bit per lane when the block size allows (VEC = 4 fp32
-// gradients or 8 bf16 gradients per unit); VEC = 1 is the scalar fallback for block
-// sizes that are not a whole number of units.
+// A lane works on units of VEC consecutive elements: VEC = 4 means one 128-bit load / store of m
+// and p and one 128-bit (fp32) or 64-bit (bf16) gradient load per unit, consecutive lanes owning
+// consecutive units; VEC = 8 (bf16 only, optional) is a 128-bit gradient load beside two 128-bit
+// words of m and p; VEC = 1 is the scalar fallback for block sizes that are not whole units.
 #ifndef AM_KERNELS_H_
 #define AM_KERNELS_H_
 

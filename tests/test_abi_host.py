@@ -189,3 +189,59 @@ def test_strided_layout_matches_oracle_block_index(oracle, dtype):
     assert kind[4] == B.PATH_ROW             # one column: the block is the whole contiguous tensor
     assert kind[5] == B.PATH_ELEMENTWISE     # one row: every element its own block
     B.adam_mini_destroy_layout(h)
+
+
+def test_random_layouts_against_oracle(oracle):
+    """Seeded random tensor lists (contiguous, column-block and AdamW-mode tensors of many sizes):
+    v numbering bit-exact against the oracle, and every block size lands on a kernel family
+    that can hold it."""
+    rng = np.random.default_rng(2024)
+    for trial in range(40):
+        descs = []
+        for _ in range(int(rng.integers(1, 12))):
+            kind = rng.integers(0, 5)
+            if kind == 0:
+                bn, nb = 1, int(rng.integers(1, 5000))
+            elif kind == 1:
+                bn, nb = int(rng.integers(2, 70)), int(rng.integers(1, 200))
+            elif kind == 2:
+                bn, nb = int(rng.choice([256, 768, 1024, 4096, 5120, 11008, 13824, 14336])), int(rng.integers(1, 40))
+            elif kind == 3:
+                bn, nb = int(rng.integers(20000, 300000)), int(rng.integers(1, 4))
+            else:
+                bn, nb = int(rng.integers(1, 40000)), int(rng.integers(1, 6))
+            flags = B.FLAG_STRIDED if rng.random() < 0.3 else 0
+            descs.append((bn * nb, bn, float(rng.choice([0.0, 1.0])), flags))
+        dtype = B.GRAD_BF16 if trial % 2 else B.GRAD_F32
+        numel = [d[0] for d in descs]
+        bnum = [d[1] for d in descs]
+        strided = [bool(d[3]) for d in descs]
+        h = B.adam_mini_init_layout(descs, dtype, -1)
+        assert B.adam_mini_num_blocks(h) == oracle.num_blocks(numel, bnum)
+        voff, kind = B.adam_mini_export_layout(h)
+        for k, d in enumerate(descs):
+            assert voff[k] == oracle.block_id(numel, bnum, k, 0, strided)
+            for e in set([0, d[0] - 1] + [int(x) for x in rng.integers(0, d[0], 16)]):
+                assert B.adam_mini_block_id(h, k, e) == oracle.block_id(numel, bnum, k, e, strided)
+            nb = d[0] // d[1]
+            if d[1] == 1 or (strided[k] and d[1] == 1):
+                assert kind[k] == B.PATH_ELEMENTWISE
+            elif strided[k] and nb > 1:
+                assert kind[k] == B.PATH_STRIDED
+            elif d[1] % 4 != 0:
+                # scalar-unit fallback: a team holds at most 6144 one-element units
+                assert kind[k] == (B.PATH_ROW if d[1] <= 6144 else B.PATH_LARGE)
+            elif d[1] <= 24576:
+                assert kind[k] == B.PATH_ROW
+            else:
+                g_bytes = d[1] * (2 if dtype == B.GRAD_BF16 else 4)
+                native = 4
+                if g_bytes <= 150 * 1024 and d[1] % native == 0:
+                    assert kind[k] == B.PATH_ROW_LDS
+                else:
+                    assert kind[k] == B.PATH_LARGE
+        infos = B.adam_mini_profile_read(h)
+        assert sum(b["n_tensors"] for b in infos) == len(descs)
+        assert sum(b["numel"] for b in infos) == sum(numel)
+        assert sum(b["n_blocks"] for b in infos) == B.adam_mini_num_blocks(h)
+        B.adam_mini_destroy_layout(h)

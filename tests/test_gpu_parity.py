@@ -249,3 +249,78 @@ def test_strided_column_blocks(grad_dtype, oracle):
         want = oracle.block_ids_tensor(numel, bnum, k, strided).astype(np.int64)
         assert np.array_equal(got.cpu().numpy(), want), "tensor %d %s" % (k, specs[k].shape)
     run.close()
+
+
+def test_step_can_be_captured_in_a_hip_graph():
+    """adam_mini_step enqueues kernels only (no memset, no allocation after the first call), so a
+    warmed-up step can be captured and replayed; every replay must equal the same eager step bit
+    for bit, with eager work and synchronisation between the replays."""
+    import gpu_harness as H
+    import torch
+    shapes = [(64, 4096), (3, 49152), (2, 524288), (500, 128), (40, 1), (7, 333)]
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    runs = []
+    for _ in range(2):
+        wl = _wl(shapes, "bf16", steps=3)
+        run = H.GpuRun(wl.specs, "bf16")
+        torch.manual_seed(5)
+        for k, s in enumerate(wl.specs):
+            run.p[k].copy_(torch.randn(s.numel) * 0.02)
+            run.g[k].copy_((torch.randn(s.numel) * 1e-3).to(torch.bfloat16))
+        for t in (1, 2, 3):
+            run.opt.step(step=t, **hp)
+        torch.cuda.synchronize()
+        runs.append(run)
+    eager, graphed = runs
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        graphed.opt.step(step=4, **hp)          # captured, not executed
+    for replay in range(3):
+        eager.opt.step(step=4, **hp)
+        graph.replay()
+        torch.cuda.synchronize()
+        scratch = torch.randn(1 << 20, device="cuda").sum().item()      # unrelated eager work between replays
+        assert scratch == scratch
+        for a, b in zip(eager.p + eager.m + [eager.v], graphed.p + graphed.m + [graphed.v]):
+            assert torch.equal(a, b), "replay %d differs from the eager step" % replay
+    for run in runs:
+        run.close()
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_random_layouts(seed, oracle):
+    """Seeded random tensor lists mixing every family, both layouts, odd sizes: parity and block ids."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import workloads
+    from paper_2406_16793_amd.partition import TensorSpec
+    rng = np.random.default_rng(seed)
+    specs = []
+    for i in range(int(rng.integers(6, 16))):
+        kind = rng.integers(0, 5)
+        if kind == 0:
+            bn, nb = 1, int(rng.integers(1, 20000))
+        elif kind == 1:
+            bn, nb = int(rng.integers(2, 300)), int(rng.integers(1, 600))
+        elif kind == 2:
+            bn, nb = int(rng.choice([256, 768, 1024, 4096, 5120, 11008, 14336])), int(rng.integers(1, 30))
+        elif kind == 3:
+            bn, nb = int(rng.integers(24000, 400000)), int(rng.integers(1, 4))
+        else:
+            bn, nb = int(rng.integers(1, 30000)), int(rng.integers(1, 8))
+        strided = bool(rng.random() < 0.3)
+        shape = (bn, nb) if strided else (nb, bn)
+        specs.append(TensorSpec("r%d" % i, shape, bn, float(rng.choice([0.0, 1.0])), strided))
+    grad_dtype = "bf16" if seed % 2 else "f32"
+    wl = workloads.Workload("random%d" % seed, 100 + seed, specs, grad_dtype, 3,
+                            rtol=5e-3 if grad_dtype == "bf16" else 1e-5)
+    run, st, worst = H.run_both(wl, check_every_step=True)
+    assert worst < 1e-5
+    numel = [s.numel for s in specs]
+    bnum = [s.block_numel for s in specs]
+    strided = [s.strided for s in specs]
+    for k in range(len(specs)):
+        got = run.opt.block_ids(k)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.block_ids_tensor(numel, bnum, k, strided).astype(np.int64))
+    run.close()
