@@ -117,7 +117,7 @@ def gpt2_small() -> Workload:
 
 
 def gpt2_small_bf16() -> Workload:
-    """GPT-2-small shape with bf16 gradients (not a BASELINE configuration): its 64x768 query / key
+    """GPT-2-small shape with bf16 gradients (an extra configuration, not one of the five benchmark ones): its 64x768 query / key
     head blocks carry 96 KB of gradient each, the case served by the LDS-staged kernel."""
     wl = gpt2_small()
     wl.name, wl.config_id, wl.grad_dtype, wl.rtol = "gpt2_small_bf16", 6, "bf16", 5e-3
@@ -126,8 +126,8 @@ def gpt2_small_bf16() -> Workload:
 
 def gpt2_small_whole() -> Workload:
     """GPT-2-small tensors under the paper's "Partition for non-Transformers" (Appendix B):
-    every tensor is ONE block (38.6 M elements for the embedding), fp32 gradients.  Not a BASELINE
-    configuration; it exercises the multi-workgroup path on whole-tensor blocks."""
+    every tensor is ONE block (38.6 M elements for the embedding), fp32 gradients.  Not one of the
+    five benchmark configurations; it exercises the multi-workgroup path on whole-tensor blocks."""
     from .partition import partition_whole
     wl = gpt2_small()
     wl.specs = partition_whole([(s.name, s.shape) for s in wl.specs])
@@ -137,7 +137,7 @@ def gpt2_small_whole() -> Workload:
 
 def llama2_7b_value_whole() -> Workload:
     """Llama-2-7B shape with the appendix's value "strategy II": each value matrix is one
-    16.8 M-element block instead of 4096 row blocks.  Not a BASELINE configuration."""
+    16.8 M-element block instead of 4096 row blocks.  Not one of the five benchmark configurations."""
     specs = partition_transformer(_llama_shapes(32, 4096, 32, 32, 11008, 32000), n_heads=32, value_whole=True)
     return Workload("llama2_7b_value_whole", 8, specs, "bf16", 5, rtol=5e-3)
 
@@ -145,7 +145,7 @@ def llama2_7b_value_whole() -> Workload:
 def llama2_7b_lora() -> Workload:
     """Rank-128 LoRA adapters on the seven linear maps of every Llama-2-7B layer: 448 small
     matrices A [128, in] and B [out, 128], partitioned by output neuron (rows of 4096 / 11008 /
-    128 elements), no weight decay, bf16 gradients.  Not a BASELINE configuration; it stresses
+    128 elements), no weight decay, bf16 gradients.  Not one of the five benchmark configurations; it stresses
     the multi-tensor packing and launch overhead rather than bandwidth."""
     r, d, f = 128, 4096, 11008
     names = []
@@ -163,7 +163,7 @@ def llama2_7b_lora() -> Workload:
 def llama2_7b_embed_t() -> Workload:
     """Llama-2-7B shape whose embedding and output matrices are stored transposed ([4096, 32000]),
     so their per-token blocks are the columns of the stored matrix (the re-ordering case of the
-    paper's Appendix D).  Not a BASELINE configuration."""
+    paper's Appendix D).  Not one of the five benchmark configurations."""
     from .partition import transposed
     wl = llama2_7b()
     wl.specs = [transposed(s) if (s.name.startswith("embed") or s.name.startswith("output")) else s
