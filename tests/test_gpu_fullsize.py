@@ -46,3 +46,22 @@ def test_full_size_sampled_blocks(name, steps):
     run.close()
     del run
     torch.cuda.empty_cache()
+
+
+def test_full_size_adamw_equivalent_mode():
+    """Llama-2-7B shape with every block of size 1 (dense v, 26 bytes per parameter): sampled elements."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import partition, workloads
+    wl = workloads.get("llama2_7b")
+    wl.specs = partition.as_adamw(wl.specs)
+    wl.name = "llama2_7b_adamw"
+    need = wl.n_params * 14 + (6 << 30)
+    if torch.cuda.get_device_properties(0).total_memory < need:
+        pytest.skip("needs %.0f GB of device memory" % (need / 1e9))
+    run, worst = H.run_sampled(wl, steps=3, progress=_say)
+    _say("llama2_7b_adamw: worst normwise rel err over sampled elements %.3g" % worst)
+    assert bool(torch.isfinite(run.v).all()) and float(run.v.min()) >= 0.0
+    run.close()
+    del run
+    torch.cuda.empty_cache()
