@@ -68,18 +68,28 @@ def cpu_baseline(wl, run, hp, target_seconds):
     grads = [grad_to_host(run.g[k]) for k in idx]
     ohp = orc.Hyper.from_f32(**hp)
     n = sum(s.numel for s in specs)
-    spent, steps = 0.0, 0
-    while True:
-        t0 = time.perf_counter()
-        st.step(grads, ohp)
-        dt = time.perf_counter() - t0
-        spent += dt
-        steps += 1
-        if spent + dt > target_seconds or steps >= 2000:
-            break
-    return {"value": n * steps / spent / 1e9, "unit": "Gparams/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": "%d tensors of layer 0 (%d params, %d blocks), %d oracle steps, %.1f s"
-                      % (len(specs), n, sum(s.n_blocks for s in specs), steps, spent)}
+
+    def timed(budget):
+        spent, steps = 0.0, 0
+        while True:
+            t0 = time.perf_counter()
+            st.step(grads, ohp)
+            dt = time.perf_counter() - t0
+            spent += dt
+            steps += 1
+            if spent + dt > budget or steps >= 2000:
+                return steps, spent
+
+    cores = orc.num_threads()
+    orc.set_num_threads(1)
+    steps1, spent1 = timed(0.2 * target_seconds)          # one host thread
+    orc.set_num_threads(cores)
+    steps, spent = timed(0.8 * target_seconds)            # one thread per host core
+    return {"value": n * steps / spent / 1e9, "unit": "Gparams/s", "cores": cores, "kind": "oracle",
+            "single_thread_value": n * steps1 / spent1 / 1e9,
+            "sample": "%d tensors of layer 0 (%d params, %d blocks); %d oracle steps in %.1f s on %d threads, "
+                      "%d steps in %.1f s on 1 thread"
+                      % (len(specs), n, sum(s.n_blocks for s in specs), steps, spent, cores, steps1, spent1)}
 
 
 def main():

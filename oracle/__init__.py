@@ -65,6 +65,13 @@ class OracleLib:
     def num_threads(self) -> int:
         return int(self._lib.amo_num_threads())
 
+    def set_num_threads(self, n: int) -> None:
+        """Host threads the block loop of amo_step_tensor uses from now on (OpenMP runtime call)."""
+        f = self._lib.omp_set_num_threads
+        f.restype = None
+        f.argtypes = [ctypes.c_int]
+        f(int(n))
+
     def step_tensor(self, p: np.ndarray, m: np.ndarray, v: np.ndarray, g: np.ndarray,
                     block_numel: int, hp: "Hyper", t: int, wd_scale: float = 1.0,
                     strided: bool = False) -> None:
@@ -137,6 +144,10 @@ def default_lib() -> OracleLib:
 
 def num_threads() -> int:
     return default_lib().num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    default_lib().set_num_threads(n)
 
 
 @dataclass
