@@ -86,3 +86,37 @@ def test_gradients_are_seeded_and_shaped():
     workloads.fill_grad(h, spec2, wl2, 5, 1)
     workloads.fill_grad(f, spec2, wl2, 5, 1)
     assert torch.equal(h, f.to(torch.bfloat16))
+
+
+def test_partition_rules_on_common_parameter_names():
+    """Algorithm 3's keywords plus the spellings of widely used checkpoints."""
+    f = partition.block_numel_for
+    d, h, kv, ff, vocab = 512, 8, 2, 1376, 1000
+    hd = d // h
+    cases = [
+        ("model.embed_tokens.weight", (vocab, d), d),                      # by token
+        ("lm_head.weight", (vocab, d), d),
+        ("model.layers.3.self_attn.q_proj.weight", (d, d), hd * d),        # by head
+        ("model.layers.3.self_attn.k_proj.weight", (kv * hd, d), hd * d),  # by KEY head (GQA)
+        ("model.layers.3.self_attn.v_proj.weight", (kv * hd, d), d),       # by output neuron
+        ("model.layers.3.self_attn.o_proj.weight", (d, d), d),
+        ("model.layers.3.mlp.gate_proj.weight", (ff, d), d),
+        ("model.layers.3.mlp.down_proj.weight", (d, ff), ff),
+        ("model.layers.3.input_layernorm.weight", (d,), d),                # whole tensor
+        ("model.norm.weight", (d,), d),
+        ("layers.0.attention.wq.weight", (d, d), hd * d),
+        ("layers.0.attention.wk.weight", (kv * hd, d), hd * d),
+        ("layers.0.attention.wo.weight", (d, d), d),
+        ("layers.0.feed_forward.w2.weight", (d, ff), ff),
+        ("tok_embeddings.weight", (vocab, d), d),
+        ("output.weight", (vocab, d), d),
+        ("some.conv.kernel", (16, 3, 3, 3), 16 * 27),                      # no rule: one block
+    ]
+    for name, shape, want in cases:
+        assert f(name, shape, n_heads=h, n_kv_heads=kv) == want, name
+    with pytest.raises(ValueError):
+        f("attn.query.weight", (d + 1, d), n_heads=h)
+    t = partition.transposed(partition.TensorSpec("embed.weight", (vocab, d), d))
+    assert t.shape == (d, vocab) and t.block_numel == d and t.strided and t.n_blocks == vocab
+    with pytest.raises(ValueError):
+        partition.transposed(partition.TensorSpec("q", (d, d), hd * d))
