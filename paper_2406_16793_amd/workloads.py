@@ -135,6 +135,17 @@ def gpt2_small_whole() -> Workload:
     return wl
 
 
+def llama2_7b_whole() -> Workload:
+    """Llama-2-7B tensors with every tensor as ONE block ("Partition for non-Transformers" applied
+    to a large model: blocks of 16.8 M to 131 M elements), bf16 gradients.  Not one of the five
+    benchmark configurations; everything goes through the multi-workgroup path."""
+    from .partition import partition_whole
+    wl = llama2_7b()
+    wl.specs = partition_whole([(s.name, s.shape) for s in wl.specs])
+    wl.name, wl.config_id, wl.steps = "llama2_7b_whole", 11, 3
+    return wl
+
+
 def llama2_7b_value_whole() -> Workload:
     """Llama-2-7B shape with the appendix's value "strategy II": each value matrix is one
     16.8 M-element block instead of 4096 row blocks.  Not one of the five benchmark configurations."""
@@ -198,7 +209,7 @@ def llama2_13b() -> Workload:
 
 
 WORKLOADS = {"tiny": tiny, "gpt2_small": gpt2_small, "gpt2_small_bf16": gpt2_small_bf16,
-             "gpt2_small_whole": gpt2_small_whole, "llama2_7b_value_whole": llama2_7b_value_whole,
+             "gpt2_small_whole": gpt2_small_whole, "llama2_7b_whole": llama2_7b_whole, "llama2_7b_value_whole": llama2_7b_value_whole,
              "llama2_7b_lora": llama2_7b_lora, "llama2_7b_embed_t": llama2_7b_embed_t, "llama2_7b": llama2_7b,
              "llama3_8b": llama3_8b, "llama2_13b": llama2_13b}
 

@@ -100,20 +100,31 @@ def compare(run: GpuRun, st: orc.OracleState, rtol: float, label="") -> float:
     return worst
 
 
-def sample_blocks(wl, per_tensor=6, large_per_tensor=2, seed=1234):
+def sample_blocks(wl, per_tensor=6, large_per_tensor=2, seed=1234, giant_budget=200_000_000):
     """Seeded choice of block indices per tensor: first, last and random ones; fewer for blocks
-    above 64K elements (attention heads) so the oracle finishes in seconds."""
+    above 64K elements (attention heads) so the oracle finishes in seconds.  Blocks above 4 M
+    elements (whole-tensor partitions) are sampled one per tensor, in a seeded order, until
+    giant_budget elements are taken; the remaining such tensors get no sample."""
     rng = np.random.default_rng(seed)
-    picks = []
-    for s in wl.specs:
+    picks = [None] * len(wl.specs)
+    budget = giant_budget
+    for k in rng.permutation(len(wl.specs)):
+        s = wl.specs[k]
         nb = s.n_blocks
+        if s.block_numel > (4 << 20):
+            if s.block_numel <= budget:
+                budget -= s.block_numel
+                picks[k] = np.array([int(rng.integers(0, nb))], dtype=np.int64)
+            else:
+                picks[k] = np.zeros(0, dtype=np.int64)
+            continue
         want = large_per_tensor if s.block_numel > 65536 else per_tensor
         if s.block_numel == 1:
             want = 4096
         idx = {0, nb - 1}
         while len(idx) < min(want, nb):
             idx.add(int(rng.integers(0, nb)))
-        picks.append(np.array(sorted(idx), dtype=np.int64))
+        picks[k] = np.array(sorted(idx), dtype=np.int64)
     return picks
 
 
@@ -126,6 +137,7 @@ def run_sampled(wl: workloads.Workload, steps=None, per_tensor=6, large_per_tens
     run = GpuRun(wl.specs, wl.grad_dtype)
     picks = sample_blocks(wl, per_tensor, large_per_tensor)
     dev_picks = [torch.from_numpy(ix).to(run.dev) for ix in picks]
+    active = [k for k in range(len(wl.specs)) if len(picks[k]) > 0]      # tensors the oracle follows
 
     def gather(tensors, k):
         # sampled blocks as contiguous rows; for column blocks that is the transposed selection, which
@@ -138,16 +150,18 @@ def run_sampled(wl: workloads.Workload, steps=None, per_tensor=6, large_per_tens
     p0 = []
     for k, s in enumerate(wl.specs):
         run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
-        p0.append(gather(run.p, k).cpu().numpy().reshape(-1))
-    st = orc.OracleState([len(ix) * s.block_numel for ix, s in zip(picks, wl.specs)],
-                         [s.block_numel for s in wl.specs], [s.wd_scale for s in wl.specs], p0)
+        if k in active:
+            p0.append(gather(run.p, k).cpu().numpy().reshape(-1))
+    st = orc.OracleState([len(picks[k]) * wl.specs[k].block_numel for k in active],
+                         [wl.specs[k].block_numel for k in active], [wl.specs[k].wd_scale for k in active], p0)
     hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
     ohp = orc.Hyper.from_f32(**hp)
     for t in range(1, steps + 1):
         host_g = []
         for k, s in enumerate(wl.specs):
             workloads.fill_grad(run.g[k], s, wl, k, t, row_chunk=8192)
-            host_g.append(grad_to_host(gather(run.g, k)).reshape(-1))
+            if k in active:
+                host_g.append(grad_to_host(gather(run.g, k)).reshape(-1))
         run.opt.step(step=t, **hp)
         st.step(host_g, ohp)
         if progress:
@@ -156,12 +170,12 @@ def run_sampled(wl: workloads.Workload, steps=None, per_tensor=6, large_per_tens
     torch.cuda.synchronize()
     worst = 0.0
     v = run.v
-    off = 0
-    for k, s in enumerate(wl.specs):
+    v_first = np.concatenate([[0], np.cumsum([s.n_blocks for s in wl.specs])])
+    for j, k in enumerate(active):
+        s = wl.specs[k]
         name = "%s[%d] %s" % (wl.name, k, s.name)
-        worst = max(worst, assert_state_close("param " + name, gather(run.p, k).cpu().numpy().reshape(-1), st.p[k], wl.rtol))
-        worst = max(worst, assert_state_close("m " + name, gather(run.m, k).cpu().numpy().reshape(-1), st.m[k], wl.rtol))
-        vk = v[off:off + s.n_blocks][dev_picks[k]].cpu().numpy()
-        worst = max(worst, assert_state_close("v " + name, vk, st.v[k], wl.rtol, is_v=True))
-        off += s.n_blocks
+        worst = max(worst, assert_state_close("param " + name, gather(run.p, k).cpu().numpy().reshape(-1), st.p[j], wl.rtol))
+        worst = max(worst, assert_state_close("m " + name, gather(run.m, k).cpu().numpy().reshape(-1), st.m[j], wl.rtol))
+        vk = v[int(v_first[k]):int(v_first[k + 1])][dev_picks[k]].cpu().numpy()
+        worst = max(worst, assert_state_close("v " + name, vk, st.v[j], wl.rtol, is_v=True))
     return run, worst

@@ -29,7 +29,7 @@ def _check_global_properties(run, wl):
 
 
 @pytest.mark.parametrize("name,steps", [("llama2_7b", 10), ("llama3_8b", 10), ("llama2_13b", 5), ("llama2_7b_value_whole", 3),
-                                        ("llama2_7b_embed_t", 3)])
+                                        ("llama2_7b_embed_t", 3), ("llama2_7b_whole", 2)])
 def test_full_size_sampled_blocks(name, steps):
     import gpu_harness as H
     import torch
