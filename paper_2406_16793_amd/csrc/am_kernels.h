@@ -460,8 +460,6 @@ __global__ __launch_bounds__(THREADS) void am_large_ids(AM_TABLE_PARAMS,
 //   am_strided_finalize  per column: fixed-order sum over the row chunks (double), v update, step scale
 //   am_strided_update    per item: m and p update with the per-column step scales
 // ===========================================================================
-constexpr int kStridedThreads = 256;
-constexpr int kStridedRows = 16;   // rows per work item
 constexpr int kStridedUnroll = 4;  // rows in flight per thread
 
 struct AmStridedItem {

@@ -144,7 +144,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       // a row must be a whole number of units, and the tensor's v slice 16-byte aligned for the scale loads
       var.vec = (ti.n_blocks % (uint64_t)native == 0) ? native : 1;
       var.lanes = 256;
-      var.upt = 16;
+      var.upt = kStridedRows;
     } else {
       var = am_choose_variant(grad_dtype, d.numel, d.block_numel, ti.v_first, tuning);
     }
@@ -179,8 +179,8 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       const uint64_t rows = d.block_numel, cols = ti.n_blocks;
       s.row_len = cols;
       s.units_per_block = cols / (uint64_t)var.vec;                        // units per stored row
-      const uint64_t groups = (s.units_per_block + 255) / 256;             // column groups of 256 units
-      const uint64_t row_chunks = (rows + 15) / 16;                        // 16 rows per work item
+      const uint64_t groups = (s.units_per_block + kStridedThreads - 1) / kStridedThreads;  // column groups
+      const uint64_t row_chunks = (rows + kStridedRows - 1) / kStridedRows;                 // rows per work item
       if (groups >= (1ull << 31) || cols >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
       s.chunks_per_block = (uint32_t)groups;
       s.aux = bk.n_partials;                                               // partial sums: [row_chunks][cols]

@@ -48,6 +48,11 @@ struct AmTable {
   uint32_t n_segs;
 };
 
+// Tile of the STRIDED family, shared by the layout builder and the kernels: a workgroup of
+// kStridedThreads lanes owns kStridedThreads units of a row over kStridedRows consecutive rows.
+constexpr int kStridedThreads = 256;
+constexpr int kStridedRows = 16;
+
 // Per-step scalars, computed on the host in double and rounded once to fp32.
 struct AmScalars {
   float beta1;      // beta1
