@@ -231,6 +231,11 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *   "row_blocked"        1: each wavefront of a row team owns a contiguous span of the block
  *   "stream_wg_per_cu"   the same cap for the AdamW-equivalent and large-block update kernels
  *   "strided_wg_per_cu"  the same cap for the column-block (ADAM_MINI_FLAG_STRIDED) update kernel
+ *   "xcd_chunk"          row kernels: a power of two C > 0 makes each of the 8 XCDs (dies with an L2 of
+ *                        their own, fed workgroups round-robin) walk runs of C consecutive workgroup
+ *                        passes instead of every 8th one; 0 keeps the hardware order
+ *   "xcd_chunk_stream"   the same for the AdamW-equivalent and large-block kernels
+ *   "xcd_chunk_strided"  the same for the column-block kernels
  *   "reset"              restore the defaults (value ignored)
  * Returns ADAM_MINI_INVALID_ARG for an unknown key or a negative value.
  */

@@ -124,7 +124,7 @@ uint32_t grid_for(uint64_t groups, const AmTuning& t) {
   return (uint32_t)g;
 }
 
-#define AM_TAB tab.segs, tab.item_keys, tab.lblock_keys, tab.n_segs
+#define AM_TAB tab.segs, tab.item_keys, tab.lblock_keys, tab.n_segs, tab.xcd_shift
 
 // Launch one kernel with an optional occupancy cap (see lds_for_cap).
 template <typename K, typename... Args>
@@ -148,7 +148,7 @@ int64_t row_cap(const AmBucket& bk, int teams, size_t grad_bytes, const AmTuning
   const uint64_t wg_bytes = units * (uint64_t)bk.var.vec * (8 + grad_bytes) * (uint64_t)teams;
   if (wg_bytes <= 24 * 1024) return 0;  // small workgroups: the wave-slot limit of a CU is cap enough
   int64_t cap = (int64_t)(((uint64_t)t.row_inflight_kb * 1024 + wg_bytes - 1) / (wg_bytes ? wg_bytes : 1));
-  if (cap < 3) cap = 3;
+  if (cap < 2) cap = 2;
   return cap > 16 ? 0 : cap;  // beyond 16 the hardware's own limits bind first
 }
 
@@ -343,6 +343,16 @@ AmTable bucket_table(const adam_mini_layout* L, const AmBucket& bk) {
   tab.item_keys = L->keys_dev + bk.table_offset;
   tab.lblock_keys = L->keys_dev + L->host.n_segs + bk.table_offset;
   tab.n_segs = (uint32_t)bk.segs.size();
+  const AmTuning& t = L->host.tuning;
+  const int fam = bk.var.family;
+  const int64_t chunk = (fam == AM_FAM_ROW || fam == AM_FAM_ROW_LDS) ? t.xcd_chunk
+                        : fam == AM_FAM_STRIDED                      ? t.xcd_chunk_strided
+                                                                     : t.xcd_chunk_stream;
+  tab.xcd_shift = 32;  // identity
+  if (chunk > 0) {
+    tab.xcd_shift = 0;
+    while ((int64_t(1) << (tab.xcd_shift + 1)) <= chunk) ++tab.xcd_shift;
+  }
   return tab;
 }
 
@@ -502,6 +512,11 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "row_blocked") g_tuning.row_blocked = value;
   else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
   else if (k == "strided_wg_per_cu") g_tuning.strided_wg_per_cu = value;
+  else if (k == "xcd_chunk" || k == "xcd_chunk_stream" || k == "xcd_chunk_strided") {
+    if (value > (int64_t(1) << 20) || (value & (value - 1)) != 0) return ADAM_MINI_INVALID_ARG;
+    (k == "xcd_chunk" ? g_tuning.xcd_chunk : k == "xcd_chunk_stream" ? g_tuning.xcd_chunk_stream
+                                                                      : g_tuning.xcd_chunk_strided) = value;
+  }
   else return ADAM_MINI_INVALID_ARG;
   return ADAM_MINI_OK;
 }

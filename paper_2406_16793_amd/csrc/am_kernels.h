@@ -27,6 +27,23 @@
   const AmSeg* __restrict__ segs, const uint32_t* __restrict__ item_keys,                     \
       const uint32_t* __restrict__ lblock_keys, uint32_t n_segs
 #define AM_TABLE_ARGS segs, item_keys, lblock_keys, n_segs
+// What every work-item kernel takes: the tables and the XCD swizzle of its workgroup passes.
+#define AM_KERNEL_PARAMS AM_TABLE_PARAMS, uint32_t xcd_shift
+
+// Workgroup pass -> group of work items.  The hardware deals consecutive workgroups round-robin to
+// the 8 XCDs, each with an L2 of its own, so with the identity map the 8 dies interleave at the
+// grain of single work items over the whole address range.  The swizzle hands each die runs of
+// 2^xcd_shift consecutive groups instead: passes b, b+8, b+16, ... (all on die b % 8) walk one run,
+// and the 8 runs of a span of 8 * 2^xcd_shift groups go to the 8 dies.  It is a bijection on
+// [0, n_groups): whole spans are permuted, the ragged tail keeps the identity.  xcd_shift >= 32
+// switches it off.  Only the order in which blocks are visited changes, never a block's arithmetic.
+__device__ __forceinline__ uint32_t am_xcd_swizzle(uint32_t b, uint32_t n_groups, uint32_t xcd_shift) {
+  if (xcd_shift >= 32) return b;
+  const uint32_t span_shift = xcd_shift + 3;
+  if (b >= (n_groups >> span_shift) << span_shift) return b;
+  const uint32_t die = b & 7u, j = b >> 3;
+  return ((((j >> xcd_shift) << 3) + die) << xcd_shift) + (j & ((1u << xcd_shift) - 1u));
+}
 
 // ===========================================================================
 // ROW family
@@ -83,14 +100,16 @@ __device__ __forceinline__ uint64_t am_row_unit(int k, uint32_t blocked) {
 }
 
 template <typename G, int VEC, int LANES, int UPT>
-__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(AM_TABLE_PARAMS, uint32_t n_items,
+__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                       uint32_t blocked, float* __restrict__ v,
                                                                       AmScalars sc) {
   using Geom = AmRowGeom<LANES>;
   // slot [parity][w] = sum of wavefront w; slot [parity][WAVES] = the block's old v
   __shared__ float xch[2][(Geom::WAVES > 1 ? Geom::WAVES : 1) + 1];
   uint32_t parity = 0;
-  for (uint32_t first = blockIdx.x * Geom::TEAMS; first < n_items; first += gridDim.x * Geom::TEAMS, parity ^= 1u) {
+  const uint32_t n_groups = (n_items + Geom::TEAMS - 1) / Geom::TEAMS;
+  for (uint32_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x, parity ^= 1u) {
+    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_shift) * Geom::TEAMS;
     const AmRowItem it = am_row_decode<LANES>(AM_TABLE_ARGS, n_items, first);
     const AmSeg& S = *it.seg;
     const uint64_t units = S.units_per_block;
@@ -162,12 +181,14 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(AM_TABLE_P
 
 // Same walk, writing the v index of every element of tensor `tensor`.
 template <int VEC, int LANES, int UPT>
-__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_TABLE_PARAMS,
+__global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_KERNEL_PARAMS,
                                                                    uint32_t n_items, uint32_t blocked,
                                                                    uint32_t tensor,
                                                                    uint64_t* __restrict__ ids) {
   using Geom = AmRowGeom<LANES>;
-  for (uint32_t first = blockIdx.x * Geom::TEAMS; first < n_items; first += gridDim.x * Geom::TEAMS) {
+  const uint32_t n_groups = (n_items + Geom::TEAMS - 1) / Geom::TEAMS;
+  for (uint32_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_shift) * Geom::TEAMS;
     const AmRowItem it = am_row_decode<LANES>(AM_TABLE_ARGS, n_items, first);
     const AmSeg& S = *it.seg;
     if (!it.active || S.tensor != tensor) continue;
@@ -199,14 +220,15 @@ __device__ __forceinline__ uint64_t am_lds_unit(uint64_t i, int j) {
 }
 
 template <typename G, int VEC>
-__global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_TABLE_PARAMS, uint32_t n_items,
+__global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                     float* __restrict__ v, AmScalars sc) {
   using Raw = typename AmRaw<G, VEC>::T;
   extern __shared__ __attribute__((aligned(16))) unsigned char am_stage_bytes[];
   Raw* stage = reinterpret_cast<Raw*>(am_stage_bytes);
   __shared__ float xch[2][kLdsRowThreads / 64 + 1];
   uint32_t parity = 0;
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x, parity ^= 1u) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x, parity ^= 1u) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmRowItem it = am_row_decode<kLdsRowThreads>(AM_TABLE_ARGS, n_items, item);
     const AmSeg& S = *it.seg;
     const uint64_t units = S.units_per_block;
@@ -283,9 +305,10 @@ __global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_TABLE_PAR
 }
 
 template <int VEC>
-__global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_ids(AM_TABLE_PARAMS, uint32_t n_items,
+__global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_ids(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                  uint32_t tensor, uint64_t* __restrict__ ids) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmRowItem it = am_row_decode<kLdsRowThreads>(AM_TABLE_ARGS, n_items, item);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;
@@ -338,11 +361,13 @@ __device__ __forceinline__ uint64_t am_chunk_unit(uint64_t unit0, int k) {
 // chunk of THREADS*UPT units 64 at a time, so there is no LDS traffic and no barrier, and a
 // workgroup reads four times the bytes of one update-kernel item.
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(256) void am_large_partial(AM_TABLE_PARAMS,
+__global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
                                                         uint32_t n_items, float* __restrict__ partials) {
   constexpr int STEPS = THREADS * UPT / 64;  // units per lane
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (uint32_t first = blockIdx.x * 4; first < n_items; first += gridDim.x * 4) {
+  const uint32_t n_groups = (n_items + 3) / 4;
+  for (uint32_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_shift) * 4;
     uint32_t item = first + wave;
     const bool active = item < n_items;
     if (!active) item = n_items - 1;
@@ -372,7 +397,7 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_TABLE_PARAMS,
 
 // One wavefront per large block: sums the block's chunk partials in a fixed order
 // (lane-strided, then butterfly) in double, updates v and stores the step scale.
-__global__ __launch_bounds__(256) void am_large_finalize(AM_TABLE_PARAMS,
+__global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS,
                                                          uint32_t n_lblocks, const float* __restrict__ partials,
                                                          float* __restrict__ v, float* __restrict__ scales,
                                                          AmScalars sc) {
@@ -397,10 +422,11 @@ __global__ __launch_bounds__(256) void am_large_finalize(AM_TABLE_PARAMS,
 }
 
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_large_update(AM_TABLE_PARAMS,
+__global__ __launch_bounds__(THREADS) void am_large_update(AM_KERNEL_PARAMS,
                                                            uint32_t n_items, const float* __restrict__ scales,
                                                            AmScalars sc) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     const float scale = scales[it.lblock];
@@ -431,10 +457,11 @@ __global__ __launch_bounds__(THREADS) void am_large_update(AM_TABLE_PARAMS,
 }
 
 template <int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_large_ids(AM_TABLE_PARAMS,
+__global__ __launch_bounds__(THREADS) void am_large_ids(AM_KERNEL_PARAMS,
                                                         uint32_t n_items, uint32_t tensor,
                                                         uint64_t* __restrict__ ids) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;
@@ -484,9 +511,10 @@ __device__ __forceinline__ AmStridedItem am_strided_decode(AM_TABLE_PARAMS, uint
 }
 
 template <typename G, int VEC>
-__global__ __launch_bounds__(kStridedThreads) void am_strided_partial(AM_TABLE_PARAMS, uint32_t n_items,
+__global__ __launch_bounds__(kStridedThreads) void am_strided_partial(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                       float* __restrict__ partials) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
     const AmSeg& S = *it.seg;
     const uint64_t rows = S.block_numel, row_len = S.row_len;
@@ -520,7 +548,7 @@ __global__ __launch_bounds__(kStridedThreads) void am_strided_partial(AM_TABLE_P
 }
 
 // One thread per column of the bucket.
-__global__ __launch_bounds__(256) void am_strided_finalize(AM_TABLE_PARAMS, uint32_t n_cols,
+__global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uint32_t n_cols,
                                                            const float* __restrict__ partials,
                                                            float* __restrict__ v, float* __restrict__ scales,
                                                            AmScalars sc) {
@@ -541,10 +569,11 @@ __global__ __launch_bounds__(256) void am_strided_finalize(AM_TABLE_PARAMS, uint
 }
 
 template <typename G, int VEC>
-__global__ __launch_bounds__(kStridedThreads) void am_strided_update(AM_TABLE_PARAMS, uint32_t n_items,
+__global__ __launch_bounds__(kStridedThreads) void am_strided_update(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                      const float* __restrict__ scales,
                                                                      AmScalars sc) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
     const AmSeg& S = *it.seg;
     const uint64_t rows = S.block_numel, row_len = S.row_len;
@@ -585,9 +614,10 @@ __global__ __launch_bounds__(kStridedThreads) void am_strided_update(AM_TABLE_PA
 }
 
 template <int VEC>
-__global__ __launch_bounds__(kStridedThreads) void am_strided_ids(AM_TABLE_PARAMS, uint32_t n_items,
+__global__ __launch_bounds__(kStridedThreads) void am_strided_ids(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                   uint32_t tensor, uint64_t* __restrict__ ids) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor || !it.lane_on) continue;
@@ -619,9 +649,10 @@ __device__ __forceinline__ AmTileItem am_tile_decode(AM_TABLE_PARAMS, uint32_t i
 }
 
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_elementwise(AM_TABLE_PARAMS,
+__global__ __launch_bounds__(THREADS) void am_elementwise(AM_KERNEL_PARAMS,
                                                           uint32_t n_items, float* __restrict__ v, AmScalars sc) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmTileItem it = am_tile_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     float* __restrict__ vt = v + S.v_first;
@@ -659,10 +690,11 @@ __global__ __launch_bounds__(THREADS) void am_elementwise(AM_TABLE_PARAMS,
 }
 
 template <int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_elementwise_ids(AM_TABLE_PARAMS,
+__global__ __launch_bounds__(THREADS) void am_elementwise_ids(AM_KERNEL_PARAMS,
                                                               uint32_t n_items, uint32_t tensor,
                                                               uint64_t* __restrict__ ids) {
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
     const AmTileItem it = am_tile_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;

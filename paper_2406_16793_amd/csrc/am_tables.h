@@ -46,6 +46,7 @@ struct AmTable {
   const uint32_t* item_keys;    // [n_segs] ascending
   const uint32_t* lblock_keys;  // [n_segs] ascending (LARGE only; otherwise zeros)
   uint32_t n_segs;
+  uint32_t xcd_shift;           // log2 of the run of work-item groups one XCD walks; >= 32: identity order
 };
 
 // Tile of the STRIDED family, shared by the layout builder and the kernels: a workgroup of

@@ -118,6 +118,11 @@ def test_set_option_validation():
     B.adam_mini_destroy_layout(h)
     with pytest.raises(B.AdamMiniError):
         B.adam_mini_set_option("lds_max_bytes", 200 * 1024)          # more than a compute unit has
+    for key in ("xcd_chunk", "xcd_chunk_stream", "xcd_chunk_strided"):
+        with pytest.raises(B.AdamMiniError):
+            B.adam_mini_set_option(key, 48)                          # not a power of two
+        B.adam_mini_set_option(key, 0)
+        B.adam_mini_set_option(key, 128)
     B.adam_mini_set_option("reset", 0)
     h = B.adam_mini_init_layout([(4096 * 8, 4096 * 2, 1.0)], B.GRAD_F32, -1)
     assert B.adam_mini_export_layout(h)[1] == [B.PATH_ROW]

@@ -287,6 +287,43 @@ def test_step_can_be_captured_in_a_hip_graph():
         run.close()
 
 
+# enough work items per family for several whole spans of 8 * chunk workgroup passes and a ragged tail
+SWIZZLE_SHAPES = [(1500, 64), (1100, 256), (300, 4096), (70, 11008), (3, 200000), (300001, 1), (5, 36000)]
+
+
+def test_xcd_swizzle_visits_every_item_once_and_keeps_the_bits(oracle):
+    """The workgroup-pass -> work-item permutation only changes the order of visits: block ids stay
+    bit-exact against the oracle and p, m, v bitwise equal to the identity order, for every chunk."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import binding as B, workloads
+    specs = H.make_specs(SWIZZLE_SHAPES) + H.make_specs([(1024, 2048), (300, 1028)], strided=True)
+    numel = [s.numel for s in specs]
+    bnum = [s.block_numel for s in specs]
+    strided = [s.strided for s in specs]
+    want_ids = [oracle.block_ids_tensor(numel, bnum, k, strided).astype(np.int64) for k in range(len(specs))]
+    wl = workloads.Workload("swizzle", 93, specs, "bf16", 2, rtol=5e-3)
+    ref = None
+    try:
+        for chunk in (0, 2, 4, 16, 64):
+            for key in ("xcd_chunk", "xcd_chunk_stream", "xcd_chunk_strided"):
+                B.adam_mini_set_option(key, chunk)
+            run, st, worst = H.run_both(wl)
+            assert worst < 1e-5, chunk
+            for k in range(len(specs)):
+                got = run.opt.block_ids(k)
+                torch.cuda.synchronize()
+                assert np.array_equal(got.cpu().numpy(), want_ids[k]), "chunk %d tensor %d" % (chunk, k)
+            state = [x.clone() for x in run.p] + [x.clone() for x in run.m] + [run.v.clone()]
+            if ref is None:
+                ref = state
+            for a, b in zip(ref, state):
+                assert torch.equal(a, b), "chunk %d changes the result bits" % chunk
+            run.close()
+    finally:
+        B.adam_mini_set_option("reset", 0)
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3, 4])
 def test_random_layouts(seed, oracle):
     """Seeded random tensor lists mixing every family, both layouts, odd sizes: parity and block ids."""
