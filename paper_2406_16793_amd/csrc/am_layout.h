@@ -47,7 +47,7 @@ struct AmTuning {
   int64_t large_chunk_upt = 4;      // LARGE: units per thread of a 256-thread chunk (1, 2, 4, 8 or 16)
   int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (1, 2, 4 or 8)
   int64_t grid_cap = 0;             // > 0: at most this many workgroups per launch (grid-stride beyond)
-  int64_t row_inflight_kb = 120;    // row kernel: resident workgroups per compute unit are capped so that the
+  int64_t row_inflight_kb = 80;     // row kernel: resident workgroups per compute unit are capped so that the
                                     //   loads they keep in flight stay near this many KB (0 = no cap)
   int64_t row_wg_per_cu = 0;        // > 0: fixed cap on resident row-kernel workgroups per compute unit (overrides row_inflight_kb)
   int64_t row_blocked = 0;          // 1: each wavefront of a row team owns a contiguous span of the block
