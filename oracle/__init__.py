@@ -24,6 +24,9 @@ GRAD_F32 = 0
 GRAD_BF16 = 1
 GRAD_F64 = 2
 
+# statistic of g .* g that feeds v: "mean" is Algorithm 1; the others are the ablation's candidates
+REDUCERS = {"mean": 0, "norm1": 1, "norm2": 2, "max": 3, "min": 4}
+
 
 def compile_c(src: str, out: str) -> str:
     """gcc one C file into a shared library (a second or two)."""
@@ -51,7 +54,7 @@ class OracleLib:
         u64, dbl, vp = ctypes.c_uint64, ctypes.c_double, ctypes.c_void_p
         lib.amo_step_tensor.restype = ctypes.c_int
         lib.amo_step_tensor.argtypes = [vp, vp, vp, vp, ctypes.c_int, u64, u64, ctypes.c_int,
-                                        dbl, dbl, dbl, dbl, dbl, u64]
+                                        dbl, dbl, dbl, dbl, dbl, u64, ctypes.c_int]
         lib.amo_block_id.restype = u64
         lib.amo_block_id.argtypes = [vp, vp, vp, ctypes.c_uint32, ctypes.c_uint32, u64]
         lib.amo_block_ids_tensor.restype = ctypes.c_int
@@ -74,11 +77,12 @@ class OracleLib:
 
     def step_tensor(self, p: np.ndarray, m: np.ndarray, v: np.ndarray, g: np.ndarray,
                     block_numel: int, hp: "Hyper", t: int, wd_scale: float = 1.0,
-                    strided: bool = False) -> None:
+                    strided: bool = False, reducer: str = "mean") -> None:
         """One step on one tensor, in place.  p, m: float64[numel]; v:
         float64[numel // block_numel]; g: float32 / float64 / uint16 (bf16 bits).
         The decay coefficient of the tensor is weight_decay * wd_scale.
-        strided: the blocks are the columns of the row-major [block_numel, n_blocks] tensor."""
+        strided: the blocks are the columns of the row-major [block_numel, n_blocks] tensor.
+        reducer: key of REDUCERS, the block statistic of g .* g ("mean": the method itself)."""
         numel = p.size
         for a in (p, m, v):
             if a.dtype != np.float64 or not a.flags.c_contiguous:
@@ -91,7 +95,7 @@ class OracleLib:
         rc = self._lib.amo_step_tensor(p.ctypes.data, m.ctypes.data, v.ctypes.data,
                                        g.ctypes.data, _grad_dtype_code(g), numel,
                                        block_numel, 1 if strided else 0, hp.lr, hp.beta1, hp.beta2,
-                                       hp.eps, lam, t)
+                                       hp.eps, lam, t, REDUCERS[reducer])
         if rc != 0:
             raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
 
@@ -176,8 +180,8 @@ def _grad_dtype_code(g: np.ndarray) -> int:
     raise TypeError("gradient must be float32, float64 or uint16 (bf16 bits), got %s" % g.dtype)
 
 
-def step_tensor(p, m, v, g, block_numel, hp, t, wd_scale=1.0, strided=False) -> None:
-    default_lib().step_tensor(p, m, v, g, block_numel, hp, t, wd_scale, strided)
+def step_tensor(p, m, v, g, block_numel, hp, t, wd_scale=1.0, strided=False, reducer="mean") -> None:
+    default_lib().step_tensor(p, m, v, g, block_numel, hp, t, wd_scale, strided, reducer)
 
 
 def block_id(numel, block_numel, tensor, elem, strided=None) -> int:
@@ -202,8 +206,10 @@ class OracleState:
 
     def __init__(self, numel: Sequence[int], block_numel: Sequence[int],
                  wd_scale: Optional[Sequence[float]], params0: Sequence[np.ndarray],
-                 lib: Optional[OracleLib] = None, strided: Optional[Sequence[bool]] = None):
+                 lib: Optional[OracleLib] = None, strided: Optional[Sequence[bool]] = None,
+                 reducer: Optional[Sequence[str]] = None):
         self.lib = lib or default_lib()
+        self.reducer = ["mean"] * len(numel) if reducer is None else [str(x) for x in reducer]
         self.strided = [False] * len(numel) if strided is None else [bool(x) for x in strided]
         self.numel = [int(x) for x in numel]
         self.block_numel = [int(x) for x in block_numel]
@@ -221,7 +227,8 @@ class OracleState:
         self.t += 1
         for k, g in enumerate(grads):
             self.lib.step_tensor(self.p[k], self.m[k], self.v[k], np.ascontiguousarray(g).reshape(-1),
-                                 self.block_numel[k], hp, self.t, self.wd_scale[k], self.strided[k])
+                                 self.block_numel[k], hp, self.t, self.wd_scale[k], self.strided[k],
+                                 self.reducer[k])
 
     def v_flat(self) -> np.ndarray:
         return np.concatenate(self.v) if self.v else np.zeros(0)

@@ -29,6 +29,15 @@
  * == numel is the non-Transformer partition (Algorithm "Partition for
  * non-Transformers", Appendix B).
  *
+ * The ablation on the design of Adam-mini (appendix section "Ablation Studies on
+ * the Design of Adam-mini") swaps the mean for other statistics taken from Adam's
+ * elementwise g .* g: its 2-norm, 1-norm, max and min.  The paper gives no
+ * formula for them; the reading taken here keeps Algorithm 1 as it stands and
+ * replaces only the word "mean" in its v line:
+ *     v = (1 - beta2) * r(g .* g) + beta2 * v,   r in {mean, 1-norm, 2-norm, max, min}
+ * with the vector norms of the n-vector g .* g written out.  `reducer` selects r;
+ * AMO_REDUCE_MEAN is the method itself.
+ *
  * Pins (tests/test_oracle_pins.py): AdamW special case against a library
  * routine, constant-gradient closed form, EMA identity, hand-worked rational
  * example, brute force against a dictionary-of-slices transcription of the
@@ -42,6 +51,12 @@
 #define AMO_GRAD_F32 0
 #define AMO_GRAD_BF16 1
 #define AMO_GRAD_F64 2
+
+#define AMO_REDUCE_MEAN 0  /* sum_i g_i^2 / n : Algorithm 1 */
+#define AMO_REDUCE_NORM1 1 /* sum_i |g_i^2| */
+#define AMO_REDUCE_NORM2 2 /* sqrt(sum_i (g_i^2)^2) */
+#define AMO_REDUCE_MAX 3   /* largest g_i^2 */
+#define AMO_REDUCE_MIN 4   /* smallest g_i^2 */
 
 /* Exact widening of one gradient element to double. */
 static double amo_grad_at(const void *g, int dtype, uint64_t i) {
@@ -65,11 +80,12 @@ static double amo_grad_at(const void *g, int dtype, uint64_t i) {
  *   g, dtype, g_first : gradient buffer, its element type, index of the block's
  *                       first element inside it (element i is g_first + i * stride)
  *   t >= 1 : step counter used by the bias corrections
+ *   reducer : AMO_REDUCE_*, the statistic of g .* g that feeds v
  */
 void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
                     uint64_t g_first, uint64_t n, uint64_t stride, double lr,
                     double beta1, double beta2, double eps, double lambda,
-                    uint64_t t) {
+                    uint64_t t, int reducer) {
   double bias1 = 1.0 - pow(beta1, (double)t);
   double bias2 = 1.0 - pow(beta2, (double)t);
 
@@ -90,7 +106,28 @@ void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
     sum_sq += gi * gi;
   }
   double mean_sq = sum_sq / (double)n;
-  *v = (1.0 - beta2) * mean_sq + beta2 * (*v);
+  double stat = mean_sq;
+  if (reducer != AMO_REDUCE_MEAN) {
+    /* the ablation's other statistics of the vector s = g .* g, s_i = g_i^2 */
+    double norm1 = 0.0, sum_s2 = 0.0, largest = 0.0, smallest = 0.0;
+    int any_nan = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+      double gi = amo_grad_at(g, dtype, g_first + i * stride);
+      double si = gi * gi;
+      norm1 += fabs(si);
+      sum_s2 += si * si;
+      if (si != si) any_nan = 1;
+      if (i == 0 || si > largest) largest = si;
+      if (i == 0 || si < smallest) smallest = si;
+    }
+    if (reducer == AMO_REDUCE_NORM1) stat = norm1;
+    if (reducer == AMO_REDUCE_NORM2) stat = sqrt(sum_s2);
+    if (reducer == AMO_REDUCE_MAX) stat = largest;
+    if (reducer == AMO_REDUCE_MIN) stat = smallest;
+    /* a comparison never selects a NaN; like the sums, max and min hand it on */
+    if (any_nan) stat = NAN;
+  }
+  *v = (1.0 - beta2) * stat + beta2 * (*v);
 
   /* v_hat = v / (1 - beta2^t) */
   double v_hat = *v / bias2;
@@ -117,16 +154,17 @@ void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
 int amo_step_tensor(double *p, double *m, double *v, const void *g, int dtype,
                     uint64_t numel, uint64_t block_numel, int strided, double lr,
                     double beta1, double beta2, double eps, double lambda,
-                    uint64_t t) {
+                    uint64_t t, int reducer) {
   if (numel == 0 || block_numel == 0 || numel % block_numel != 0 || t == 0)
     return -1;
+  if (reducer < AMO_REDUCE_MEAN || reducer > AMO_REDUCE_MIN) return -1;
   int64_t n_blocks = (int64_t)(numel / block_numel);
 #pragma omp parallel for schedule(static)
   for (int64_t b = 0; b < n_blocks; ++b) {
     uint64_t first = strided ? (uint64_t)b : (uint64_t)b * block_numel;
     uint64_t stride = strided ? (uint64_t)n_blocks : 1;
     amo_step_block(p + first, m + first, v + b, g, dtype, first, block_numel,
-                   stride, lr, beta1, beta2, eps, lambda, t);
+                   stride, lr, beta1, beta2, eps, lambda, t, reducer);
   }
   return 0;
 }

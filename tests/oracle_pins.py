@@ -424,6 +424,116 @@ def pin_strided_blocks(lib):
         raise AssertionError("strided block_ids_tensor")
 
 
+# ---------------------------------------------------------------------------
+# P10: the ablation's other block statistics ("Ablation Studies on the Design of Adam-mini":
+# 2-norm, 1-norm, max, min in place of the mean).  Reading: Algorithm 1 with r(g .* g) in its v
+# line.  Pinned by numpy's norm / max / min routines on the vector g*g, the EMA written as an
+# explicit sum, the constant-gradient closed form with rms replaced by sqrt(r), the chain
+# min <= mean <= max <= 2-norm <= 1-norm, hand values, the one-element block (every statistic is
+# the element itself, i.e. AdamW), the scaling law, NaN hand-over and the strided form.
+# ---------------------------------------------------------------------------
+def _statistic(name, s):
+    if name == "mean":
+        return float(np.mean(s))
+    if name == "norm1":
+        return float(np.linalg.norm(s, 1))
+    if name == "norm2":
+        return float(np.linalg.norm(s, 2))
+    return float(np.max(s)) if name == "max" else float(np.min(s))
+
+
+def pin_alternative_reducers(lib):
+    rng = np.random.default_rng(77)
+    names = ["mean", "norm1", "norm2", "max", "min"]
+    nb, bs, T = 5, 7, 4
+    hp = orc.Hyper(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    grads = [rng.normal(0, 1e-2, nb * bs) * np.repeat(rng.uniform(0.1, 10, nb), bs) for _ in range(T)]
+    p0 = rng.normal(0, 1.0, nb * bs)
+    vs = {}
+    for name in names:
+        p, m, v = p0.copy(), np.zeros(nb * bs), np.zeros(nb)
+        P, M = p0.copy(), np.zeros(nb * bs)
+        for t in range(1, T + 1):
+            lib.step_tensor(p, m, v, grads[t - 1].copy(), bs, hp, t, reducer=name)
+            # v_b(t) = (1 - b2) sum_k b2^(t-k) r(g_k * g_k), statistics from numpy
+            want_v = np.array([sum((1 - hp.beta2) * hp.beta2 ** (t - k) * _statistic(name, grads[k - 1][b * bs:(b + 1) * bs] ** 2)
+                                   for k in range(1, t + 1)) for b in range(nb)])
+            _close(v, want_v, 1e-12, 0, "%s: EMA of the numpy statistic, t=%d" % (name, t))
+            # the rest of Algorithm 1 around that v, vectorised
+            P = P - hp.lr * hp.weight_decay * P
+            M = (1 - hp.beta1) * grads[t - 1] + hp.beta1 * M
+            P = P - hp.lr * (M / (1 - hp.beta1 ** t)) / np.repeat(np.sqrt(want_v / (1 - hp.beta2 ** t)) + hp.eps, bs)
+            _close(p, P, 1e-11, 1e-14, "%s: param t=%d" % (name, t))
+            _close(m, M, 1e-12, 0, "%s: m t=%d" % (name, t))
+        vs[name] = v.copy()
+    if not (np.all(vs["min"] <= vs["mean"]) and np.all(vs["mean"] <= vs["max"]) and np.all(vs["max"] <= vs["norm2"])
+            and np.all(vs["norm2"] <= vs["norm1"]) and np.all(vs["min"] < vs["norm1"])):
+        raise AssertionError("min <= mean <= max <= 2-norm <= 1-norm violated")
+    # hand values: g = (1, -2, 2, 0), g*g = (1, 4, 4, 0); beta2 = 1/2, one step: v = r / 2
+    hp2 = orc.Hyper(lr=0.5, beta1=0.5, beta2=0.5, eps=0.0, weight_decay=0.0)
+    hand = {"mean": 9 / 8, "norm1": 9 / 2, "norm2": math.sqrt(33) / 2, "max": 2.0, "min": 0.0}
+    for name in names:
+        p, m, v = np.ones(4), np.zeros(4), np.zeros(1)
+        lib.step_tensor(p, m, v, np.array([1.0, -2.0, 2.0, 0.0]), 4, hp2, 1, reducer=name)
+        _close(v, [hand[name]], 1e-15, 0, "%s: hand value" % name)
+        if name != "min":     # v_hat = r, m_hat = g: param = 1 - g / (2 sqrt(r))
+            _close(p, 1 - np.array([1.0, -2.0, 2.0, 0.0]) / (2 * math.sqrt(2 * hand[name])), 1e-15, 0, "%s: hand param" % name)
+    # |g| = c over the block: mean = max = min = c^2, 1-norm = n c^2, 2-norm = sqrt(n) c^2
+    c, n = 0.25, 9
+    g = c * np.where(rng.random(n) < 0.5, -1.0, 1.0)
+    for name, want in (("mean", c * c), ("max", c * c), ("min", c * c), ("norm1", n * c * c), ("norm2", 3 * c * c)):
+        p, m, v = np.zeros(n), np.zeros(n), np.zeros(1)
+        lib.step_tensor(p, m, v, g.copy(), n, hp, 1, reducer=name)
+        _close(v, [(1 - hp.beta2) * want], 1e-15, 0, "%s: equal magnitudes" % name)
+    # constant gradient: v_hat = r(g*g) at every step, so param follows the closed form with sqrt(r) for the rms
+    g = rng.normal(0, 1e-2, nb * bs)
+    for name in names:
+        p, m, v = p0.copy(), np.zeros(nb * bs), np.zeros(nb)
+        r = np.array([_statistic(name, g[b * bs:(b + 1) * bs] ** 2) for b in range(nb)])
+        u = g / np.repeat(np.sqrt(r) + hp.eps, bs)
+        a = 1.0 - hp.lr * hp.weight_decay
+        for t in range(1, 9):
+            lib.step_tensor(p, m, v, g.copy(), bs, hp, t, reducer=name)
+        _close(p, a ** 8 * p0 - hp.lr * u * (1 - a ** 8) / (1 - a), 1e-11, 1e-14, "%s: closed-form param" % name)
+        _close(v, (1 - hp.beta2 ** 8) * r, 1e-12, 0, "%s: closed-form v" % name)
+    # one-element blocks: every statistic of a 1-vector is the element, so all five are AdamW
+    ref = None
+    for name in names:
+        p, m, v = p0.copy(), np.zeros(nb * bs), np.zeros(nb * bs)
+        for t in range(1, 4):
+            lib.step_tensor(p, m, v, grads[t - 1].copy(), 1, hp, t, reducer=name)
+        if ref is None:
+            ref = (p.copy(), v.copy())
+        _close(p, ref[0], 1e-14, 0, "%s: one-element blocks param" % name)
+        _close(v, ref[1], 1e-14, 0, "%s: one-element blocks v" % name)
+    # scaling g by alpha scales every statistic by alpha^2
+    for name in names:
+        v1, v2 = np.zeros(nb), np.zeros(nb)
+        lib.step_tensor(p0.copy(), np.zeros(nb * bs), v1, grads[0].copy(), bs, hp, 1, reducer=name)
+        lib.step_tensor(p0.copy(), np.zeros(nb * bs), v2, 4.0 * grads[0], bs, hp, 1, reducer=name)
+        _close(v2, 16.0 * v1, 1e-14, 0, "%s: scaling" % name)
+    # a NaN gradient poisons its own block under every statistic, and only that block
+    gn = grads[0].copy()
+    gn[2 * bs + 3] = np.nan
+    for name in names:
+        p, m, v = p0.copy(), np.zeros(nb * bs), np.zeros(nb)
+        lib.step_tensor(p, m, v, gn.copy(), bs, hp, 1, reducer=name)
+        if not (np.isnan(v[2]) and np.isfinite(np.delete(v, 2)).all() and np.isnan(p[2 * bs:3 * bs]).all()
+                and np.isfinite(np.delete(p, np.arange(2 * bs, 3 * bs))).all()):
+            raise AssertionError("%s: NaN hand-over" % name)
+    # strided form: bit for bit the transpose of the contiguous form
+    B, n = 6, 5
+    W0, G = rng.normal(0, 1, (B, n)), rng.normal(0, 0.1, (B, n))
+    for name in names:
+        pc, mc, vc = W0.ravel().copy(), np.zeros(B * n), np.zeros(B)
+        ps, ms, vs_ = W0.T.ravel().copy(), np.zeros(B * n), np.zeros(B)
+        lib.step_tensor(pc, mc, vc, G.ravel().copy(), n, hp, 1, reducer=name)
+        lib.step_tensor(ps, ms, vs_, G.T.ravel().copy(), n, hp, 1, reducer=name, strided=True)
+        if not (np.array_equal(ps.reshape(n, B).T.ravel(), pc) and np.array_equal(vs_, vc)):
+            raise AssertionError("%s: strided form differs from the transposed contiguous form" % name)
+
+
 ALL_PINS = [pin_hand_worked, pin_adamw_reduction, pin_constant_gradient,
             pin_ema_and_five_param_example, pin_bruteforce_partition, pin_symmetries,
-            pin_first_step, pin_grad_dtypes, pin_layout_invariants, pin_strided_blocks]
+            pin_first_step, pin_grad_dtypes, pin_layout_invariants, pin_strided_blocks,
+            pin_alternative_reducers]

@@ -17,8 +17,8 @@ MUTANTS = [
     ("sum instead of mean", "double mean_sq = sum_sq / (double)n;", "double mean_sq = sum_sq;"),
     ("mean of |g| instead of g*g", "sum_sq += gi * gi;", "sum_sq += fabs(gi);"),
     ("square of the mean", "double mean_sq = sum_sq / (double)n;", "double mean_sq = sum_sq / (double)n; mean_sq = mean_sq * mean_sq;"),
-    ("beta2 weights swapped", "*v = (1.0 - beta2) * mean_sq + beta2 * (*v);", "*v = beta2 * mean_sq + (1.0 - beta2) * (*v);"),
-    ("v not accumulated", "*v = (1.0 - beta2) * mean_sq + beta2 * (*v);", "*v = (1.0 - beta2) * mean_sq;"),
+    ("beta2 weights swapped", "*v = (1.0 - beta2) * stat + beta2 * (*v);", "*v = beta2 * stat + (1.0 - beta2) * (*v);"),
+    ("v not accumulated", "*v = (1.0 - beta2) * stat + beta2 * (*v);", "*v = (1.0 - beta2) * stat;"),
     ("no bias correction of m", "double m_hat = m[i * stride] / bias1;", "double m_hat = m[i * stride];"),
     ("no bias correction of v", "double v_hat = *v / bias2;", "double v_hat = *v;"),
     ("bias correction of m uses t+1", "double bias1 = 1.0 - pow(beta1, (double)t);", "double bias1 = 1.0 - pow(beta1, (double)t + 1.0);"),
@@ -42,6 +42,15 @@ MUTANTS = [
     ("strided block id uses division", "return blocks_before + elem % (numel[tensor] / block_numel[tensor]);", "return blocks_before + elem / block_numel[tensor];"),
     ("strided block id modulo block_numel", "return blocks_before + elem % (numel[tensor] / block_numel[tensor]);", "return blocks_before + elem % block_numel[tensor];"),
     ("bf16 shifted wrongly", "<< 16;", "<< 15;"),
+    ("reducer ignored", "if (reducer != AMO_REDUCE_MEAN) {", "if (0) {"),
+    ("1-norm divided by n", "stat = norm1;", "stat = norm1 / (double)n;"),
+    ("2-norm without the root", "stat = sqrt(sum_s2);", "stat = sum_s2;"),
+    ("2-norm of g instead of g.*g", "sum_s2 += si * si;", "sum_s2 += si;"),
+    ("max and min swapped", "if (i == 0 || si > largest) largest = si;", "if (i == 0 || si < largest) largest = si;"),
+    ("min starts from zero", "if (i == 0 || si < smallest) smallest = si;", "if (si < smallest) smallest = si;"),
+    ("statistics of |g| instead of g.*g", "double si = gi * gi;", "double si = fabs(gi);"),
+    ("max does not hand a NaN on", "if (any_nan) stat = NAN;", ""),
+    ("alternative statistic strided read with stride 1", "double gi = amo_grad_at(g, dtype, g_first + i * stride);\n      double si", "double gi = amo_grad_at(g, dtype, g_first + i);\n      double si"),
 ]
 
 
