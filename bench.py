@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--workload", default="llama2_7b",
                     help="tiny | gpt2_small | llama2_7b | llama3_8b | llama2_13b")
     ap.add_argument("--adamw", action="store_true", help="AdamW-equivalent mode: every block of size 1")
+    ap.add_argument("--reducer", default="mean", choices=["mean", "norm1", "norm2", "max", "min"],
+                    help="block statistic of g*g in the v update (mean = the method; the others are the ablation's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -112,6 +114,8 @@ def main():
     wl = workloads.get(args.workload)
     if args.adamw:
         wl.specs = partition.as_adamw(wl.specs)
+    if args.reducer != "mean":
+        wl.specs = partition.with_reducer(wl.specs, args.reducer)
     hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
 
     torch.cuda.set_device(0)
@@ -172,7 +176,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name + ("_adamw" if args.adamw else ""), "params": n_params, "blocks": n_blocks,
+        "config": {"workload": wl.name + ("_adamw" if args.adamw else "") + ("" if args.reducer == "mean" else "_" + args.reducer),
+                   "params": n_params, "blocks": n_blocks,
                    "tensors": len(wl.specs), "grad_dtype": wl.grad_dtype, "state_dtype": "f32",
                    "launches_per_step": sum(b["n_kernels"] for b in buckets)},
         "whole_step": {"algorithmic_GBps": round(whole_gbs, 1), "frac_of_peak": round(whole_gbs / HBM_PEAK_GBS, 4),

@@ -68,7 +68,23 @@ enum {
    * COLUMN j (elements r*n_blocks + j): the layout of a weight whose codebase keeps W as its
    * transpose, for which the paper's Appendix D says the blocks must be re-ordered.  Results equal
    * those of the contiguous form on the transposed data. */
-  ADAM_MINI_FLAG_STRIDED = 1u
+  ADAM_MINI_FLAG_STRIDED = 1u,
+
+  /* Bits 4-6: the block statistic r of g .* g that feeds the second moment,
+   *     v_b <- beta2 v_b + (1 - beta2) r(g_b .* g_b).
+   * MEAN (0, the default) is the method itself (Algorithm 1, Section 2.3).  The others are the
+   * candidates of the appendix's "Ablation Studies on the Design of Adam-mini", which names them
+   * (2-norm, 1-norm, max, min of Adam's elementwise g .* g) without a formula; they are read as
+   * Algorithm 1 with only the word "mean" replaced:
+   *     NORM1  sum_i g_i^2        NORM2  sqrt(sum_i g_i^4)        MAX  max_i g_i^2        MIN  min_i g_i^2
+   * A NaN in the block's gradient makes every statistic NaN.  With block_numel = 1 all five are
+   * g^2 (AdamW).  Sums are fp32 like the mean's; g^4 leaves the normal fp32 range below |g| ~ 3e-10. */
+  ADAM_MINI_REDUCE_MEAN = 0u << 4,
+  ADAM_MINI_REDUCE_NORM1 = 1u << 4,
+  ADAM_MINI_REDUCE_NORM2 = 2u << 4,
+  ADAM_MINI_REDUCE_MAX = 3u << 4,
+  ADAM_MINI_REDUCE_MIN = 4u << 4,
+  ADAM_MINI_REDUCE_MASK = 7u << 4
 };
 
 /*
@@ -85,7 +101,7 @@ typedef struct adam_mini_tensor_desc {
   uint64_t numel;       /* > 0 */
   uint64_t block_numel; /* > 0 and divides numel */
   float wd_scale;       /* lambda_k = weight_decay * wd_scale (1 for decayed tensors, 0 for none); finite, >= 0 */
-  uint32_t flags;       /* 0 or ADAM_MINI_FLAG_STRIDED; other bits are reserved and must be 0 */
+  uint32_t flags;       /* ADAM_MINI_FLAG_STRIDED and / or one ADAM_MINI_REDUCE_*; other bits are reserved and must be 0 */
 } adam_mini_tensor_desc;
 
 /* Hyper-parameters of one step (Algorithm 1, lines 1 and 5-10). */

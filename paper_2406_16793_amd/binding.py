@@ -18,6 +18,8 @@ OK, INVALID_ARG, MISALIGNED, OUT_OF_MEMORY, HIP_ERROR, NO_DEVICE = 0, -1, -2, -3
 GRAD_F32, GRAD_BF16 = 0, 1
 PATH_ELEMENTWISE, PATH_ROW, PATH_LARGE, PATH_ROW_LDS, PATH_STRIDED = 0, 1, 2, 3, 4
 FLAG_STRIDED = 1
+# adam_mini_tensor_desc.flags bits 4-6: block statistic of g*g that feeds v
+REDUCE_FLAGS = {"mean": 0 << 4, "norm1": 1 << 4, "norm2": 2 << 4, "max": 3 << 4, "min": 4 << 4}
 
 
 class TensorDesc(ctypes.Structure):
@@ -212,7 +214,8 @@ class AdamMini:
         self.grad_dtype = GRAD_BF16 if grad_dtype == "bf16" else GRAD_F32
         self.device = device
         self.layout = adam_mini_init_layout([(s.numel, s.block_numel, s.wd_scale,
-                                              FLAG_STRIDED if getattr(s, "strided", False) else 0)
+                                              (FLAG_STRIDED if getattr(s, "strided", False) else 0)
+                                              | REDUCE_FLAGS[getattr(s, "reducer", "mean")])
                                              for s in self.specs],
                                             self.grad_dtype, device)
         self.num_blocks = adam_mini_num_blocks(self.layout)

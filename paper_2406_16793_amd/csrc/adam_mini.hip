@@ -250,13 +250,19 @@ int launch_large(const AmVariant& var, const AmBucket& bk, const AmTable& tab, f
   const uint32_t fgrid = grid_for((bk.n_lblocks + 3) / 4, t);
   const uint32_t pgrid = grid_for((bk.n_items + 3) / 4, t);
 #define X(L, U)                                                                                        \
-  if (var.lanes == L && var.upt == U) {                                                                \
-    hipLaunchKernelGGL((am_large_partial<G, VEC, L, U>), dim3(pgrid), dim3(256), 0, stream, AM_TAB,     \
-                       n_items, partials);                                                             \
-    hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, AM_TAB, n_lblocks,           \
-                       (const float*)partials, v, scales, sc);                                         \
-    return launch_capped(am_large_update<G, VEC, L, U>, grid, L, t.stream_wg_per_cu, stream, AM_TAB,   \
-                         n_items, (const float*)scales, sc);                                           \
+  if constexpr (VEC * U <= 64) { /* larger chunks are never chosen: they would not fit the registers */ \
+    if (var.lanes == L && var.upt == U) {                                                              \
+      if (bk.alt_reducer)                                                                              \
+        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, true>), dim3(pgrid), dim3(256), 0, stream,  \
+                           AM_TAB, n_items, partials);                                                 \
+      else                                                                                             \
+        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, false>), dim3(pgrid), dim3(256), 0, stream, \
+                           AM_TAB, n_items, partials);                                                 \
+      hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, AM_TAB, n_lblocks,         \
+                         (const float*)partials, v, scales, sc);                                       \
+      return launch_capped(am_large_update<G, VEC, L, U>, grid, L, t.stream_wg_per_cu, stream, AM_TAB, \
+                           n_items, (const float*)scales, sc);                                         \
+    }                                                                                                  \
   }
   AM_LARGE_VARIANTS(X)
 #undef X

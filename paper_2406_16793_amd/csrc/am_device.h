@@ -191,6 +191,84 @@ __device__ __forceinline__ double am_wave_sum_f64(double x) {
 }
 
 // ---------------------------------------------------------------------------
+// Block statistics of s = g .* g that may feed v.  AM_RED_MEAN is Algorithm 1 (Section 2.3);
+// the others are the candidates of the appendix's ablation on the design of Adam-mini, read as
+// "Algorithm 1 with r(g .* g) in place of mean(g .* g)":
+//   1-norm  sum_i |s_i| = sum_i g_i^2      2-norm  sqrt(sum_i s_i^2) = sqrt(sum_i g_i^4)
+//   max     largest g_i^2                  min     smallest g_i^2
+// A NaN among the g_i makes every statistic NaN (max and min hand it on like the sums do).
+// The statistic is a tensor property (AmSeg::reducer); mean and 1-norm share the sum-of-squares
+// path, the other three run through the generic accumulate / combine functions below.
+// ---------------------------------------------------------------------------
+enum : uint32_t { AM_RED_MEAN = 0, AM_RED_NORM1 = 1, AM_RED_NORM2 = 2, AM_RED_MAX = 3, AM_RED_MIN = 4 };
+
+__device__ __forceinline__ bool am_red_is_sum_sq(uint32_t red) { return red <= AM_RED_NORM1; }
+
+template <typename T>
+__device__ __forceinline__ T am_nanmax(T a, T b) { return (b > a || b != b) ? b : a; }
+template <typename T>
+__device__ __forceinline__ T am_nanmin(T a, T b) { return (b < a || b != b) ? b : a; }
+
+// Combination of two partial results (branch-free: lanes of one wavefront may hold different reducers).
+template <typename T>
+__device__ __forceinline__ T am_combine(uint32_t red, T a, T b) {
+  const T sum = a + b, hi = am_nanmax(a, b), lo = am_nanmin(a, b);
+  return red < AM_RED_MAX ? sum : (red == AM_RED_MAX ? hi : lo);
+}
+
+// Neutral element of the combination.
+__device__ __forceinline__ float am_red_identity(uint32_t red) {
+  return red == AM_RED_MIN ? __builtin_huge_valf() : 0.0f;
+}
+
+// N more gradient elements, in order, into a lane's partial result.
+template <int N>
+__device__ __forceinline__ float am_red_accumulate(uint32_t red, const float (&g)[N], float acc) {
+  if (red == AM_RED_NORM2) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) { const float s = g[j] * g[j]; acc = fmaf(s, s, acc); }
+  } else if (red == AM_RED_MAX) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) acc = am_nanmax(acc, g[j] * g[j]);
+  } else if (red == AM_RED_MIN) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) acc = am_nanmin(acc, g[j] * g[j]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < N; ++j) acc = fmaf(g[j], g[j], acc);
+  }
+  return acc;
+}
+
+// The statistic from the fully combined result x over a block of n elements.
+__device__ __forceinline__ float am_red_finish(uint32_t red, float x, float n) {
+  return red == AM_RED_MEAN ? x / n : (red == AM_RED_NORM2 ? sqrtf(x) : x);
+}
+
+__device__ __forceinline__ float am_row16_reduce(uint32_t red, float x) {
+  x = am_combine(red, x, am_dpp<0xB1>(x));
+  x = am_combine(red, x, am_dpp<0x4E>(x));
+  x = am_combine(red, x, am_dpp<0x141>(x));
+  x = am_combine(red, x, am_dpp<0x140>(x));
+  return x;
+}
+
+__device__ __forceinline__ float am_wave_reduce(uint32_t red, float x) {
+  x = am_row16_reduce(red, x);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 48));
+  return am_combine(red, am_combine(red, r0, r1), am_combine(red, r2, r3));
+}
+
+__device__ __forceinline__ double am_wave_reduce_f64(uint32_t red, double x) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) x = am_combine(red, x, __shfl_xor(x, off, 64));
+  return x;
+}
+
+// ---------------------------------------------------------------------------
 // work-table lookup: last segment whose first key is <= key
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t am_find_seg(const uint32_t* __restrict__ keys, uint32_t n_segs, uint32_t key) {
@@ -205,11 +283,11 @@ __device__ __forceinline__ uint32_t am_find_seg(const uint32_t* __restrict__ key
 // ---------------------------------------------------------------------------
 // the arithmetic of Algorithm 1 (Section 2.3), fp32
 // ---------------------------------------------------------------------------
-// Per-block scalars: new second moment and the step scale s = (lr/bc1) / (sqrt(v/bc2) + eps).
-__device__ __forceinline__ void am_block_scalars(float sum_sq, float n, float v_old, const AmScalars& sc,
+// Per-block scalars from the block statistic (mean of g^2 in Algorithm 1): new second moment and
+// the step scale s = (lr/bc1) / (sqrt(v/bc2) + eps).
+__device__ __forceinline__ void am_block_scalars(float stat, float v_old, const AmScalars& sc,
                                                  float* v_new, float* scale) {
-  const float mean_sq = sum_sq / n;
-  const float v = fmaf(sc.beta2, v_old, sc.omb2 * mean_sq);
+  const float v = fmaf(sc.beta2, v_old, sc.omb2 * stat);
   const float v_hat = v / sc.bc2;
   const float denom = sqrtf(v_hat) + sc.eps;
   *v_new = v;

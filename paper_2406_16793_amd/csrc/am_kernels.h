@@ -137,31 +137,48 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(AM_KERNEL_
         for (int j = 0; j < VEC; ++j) gv[k][j] = 0.0f;
       }
     }
-    // sum of squares: per lane in unit order, then the fixed reduction tree
+    // block statistic: per lane in unit order, then the fixed reduction tree
+    const uint32_t red = S.reducer;
     float ss = 0.0f;
+    if (am_red_is_sum_sq(red)) {
+      // Algorithm 1's sum of squares (absent units were loaded as zeros)
 #pragma unroll
-    for (int k = 0; k < UPT; ++k)
+      for (int k = 0; k < UPT; ++k)
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) ss = fmaf(gv[k][j], gv[k][j], ss);
+        for (int j = 0; j < VEC; ++j) ss = fmaf(gv[k][j], gv[k][j], ss);
+    } else {
+      ss = am_red_identity(red);
+#pragma unroll
+      for (int k = 0; k < UPT; ++k)
+        if (it.active && am_row_unit<LANES, UPT>(k, blocked) < units) {
+          ss = am_red_accumulate(red, gv[k], ss);
+        }
+    }
 
     if constexpr (LANES == 16) {
-      ss = am_row16_sum(ss);
-    } else if constexpr (Geom::WAVES == 1) {
-      ss = am_wave_sum(ss);
+      ss = am_row16_reduce(red, ss);  // teams of one wavefront may differ in their reducer
     } else {
-      ss = am_wave_sum(ss);
-      float* slot = xch[parity];
-      if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = ss;
-      if (threadIdx.x == 0) slot[Geom::WAVES] = v_old;
-      __syncthreads();
-      ss = slot[0];
+      // whole wavefronts share the block, so the choice is uniform
+      ss = am_red_is_sum_sq(red) ? am_wave_sum(ss) : am_wave_reduce(red, ss);
+      if constexpr (Geom::WAVES > 1) {
+        float* slot = xch[parity];
+        if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = ss;
+        if (threadIdx.x == 0) slot[Geom::WAVES] = v_old;
+        __syncthreads();
+        ss = slot[0];
+        if (am_red_is_sum_sq(red)) {
 #pragma unroll
-      for (int w = 1; w < Geom::WAVES; ++w) ss += slot[w];
-      v_old = slot[Geom::WAVES];
+          for (int w = 1; w < Geom::WAVES; ++w) ss += slot[w];
+        } else {
+#pragma unroll
+          for (int w = 1; w < Geom::WAVES; ++w) ss = am_combine(red, ss, slot[w]);
+        }
+        v_old = slot[Geom::WAVES];
+      }
     }
 
     float v_new, scale;
-    am_block_scalars(ss, (float)S.block_numel, v_old, sc, &v_new, &scale);
+    am_block_scalars(am_red_finish(red, ss, (float)S.block_numel), v_old, sc, &v_new, &scale);
     const float decay = sc.lr_wd * S.wd_scale;
     if (it.active && (threadIdx.x % LANES) == 0) v[v_idx] = v_new;
 
@@ -237,8 +254,9 @@ __global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_KERNEL_PA
     float v_old = 0.0f;
     if (threadIdx.x == 0) v_old = v[v_idx];
 
-    // pass 1: HBM -> registers -> LDS, sum of squares on the way
-    float ss = 0.0f;
+    // pass 1: HBM -> registers -> LDS, block statistic on the way
+    const uint32_t red = S.reducer;
+    float ss = am_red_identity(red);
     for (uint64_t i = 0; i < steps; ++i) {
       Raw r[kLdsRowUnroll];
 #pragma unroll
@@ -253,24 +271,33 @@ __global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_KERNEL_PA
           stage[u] = r[j];
           float gv[VEC];
           am_widen(r[j], gv);
+          if (am_red_is_sum_sq(red)) {
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) ss = fmaf(gv[e], gv[e], ss);
+            for (int e = 0; e < VEC; ++e) ss = fmaf(gv[e], gv[e], ss);
+          } else {
+            ss = am_red_accumulate(red, gv, ss);
+          }
         }
       }
     }
-    ss = am_wave_sum(ss);
+    ss = am_red_is_sum_sq(red) ? am_wave_sum(ss) : am_wave_reduce(red, ss);
     float* slot = xch[parity];
     if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = ss;
     if (threadIdx.x == 0) slot[kLdsRowThreads / 64] = v_old;
     __syncthreads();  // also orders the LDS staging before pass 2 (each thread re-reads only its own units,
                       // but the barrier is needed for the sums anyway)
     ss = slot[0];
+    if (am_red_is_sum_sq(red)) {
 #pragma unroll
-    for (int w = 1; w < kLdsRowThreads / 64; ++w) ss += slot[w];
+      for (int w = 1; w < kLdsRowThreads / 64; ++w) ss += slot[w];
+    } else {
+#pragma unroll
+      for (int w = 1; w < kLdsRowThreads / 64; ++w) ss = am_combine(red, ss, slot[w]);
+    }
     v_old = slot[kLdsRowThreads / 64];
 
     float v_new, scale;
-    am_block_scalars(ss, (float)S.block_numel, v_old, sc, &v_new, &scale);
+    am_block_scalars(am_red_finish(red, ss, (float)S.block_numel), v_old, sc, &v_new, &scale);
     const float decay = sc.lr_wd * S.wd_scale;
     if (threadIdx.x == 0) v[v_idx] = v_new;
 
@@ -360,7 +387,10 @@ __device__ __forceinline__ uint64_t am_chunk_unit(uint64_t unit0, int k) {
 // Sum of g^2 of one chunk per WAVEFRONT (four chunks per 256-thread workgroup): a wavefront walks its
 // chunk of THREADS*UPT units 64 at a time, so there is no LDS traffic and no barrier, and a
 // workgroup reads four times the bytes of one update-kernel item.
-template <typename G, int VEC, int THREADS, int UPT>
+// ALT: some tensor of the bucket uses one of the ablation's other statistics.  It is a template
+// parameter because that path needs the chunk's gradient a second time from the registers, which
+// would otherwise cost the plain sum of squares its occupancy (67 -> 120 VGPRs).
+template <typename G, int VEC, int THREADS, int UPT, bool ALT>
 __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
                                                         uint32_t n_items, float* __restrict__ partials) {
   constexpr int STEPS = THREADS * UPT / 64;  // units per lane
@@ -391,6 +421,18 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
 #pragma unroll
       for (int j = 0; j < VEC; ++j) ss = fmaf(gv[k][j], gv[k][j], ss);
     ss = am_wave_sum(ss);
+    if constexpr (ALT) {
+      const uint32_t red = S.reducer;
+      if (!am_red_is_sum_sq(red)) {
+        ss = am_red_identity(red);
+#pragma unroll
+        for (int k = 0; k < STEPS; ++k)
+          if (active && it.unit0 + (uint64_t)k * 64 + lane < S.units_per_block) {
+            ss = am_red_accumulate(red, gv[k], ss);
+          }
+        ss = am_wave_reduce(red, ss);
+      }
+    }
     if (active && lane == 0) partials[item] = ss;
   }
 }
@@ -408,13 +450,19 @@ __global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS,
     const AmSeg& S = segs[s];
     const uint32_t block = lb - lblock_keys[s];
     const uint32_t first = item_keys[s] + block * S.chunks_per_block;
-    double acc = 0.0;
-    for (uint32_t c = lane; c < S.chunks_per_block; c += 64) acc += (double)partials[first + c];
-    acc = am_wave_sum_f64(acc);
+    const uint32_t red = S.reducer;
+    double acc = (double)am_red_identity(red);
+    if (am_red_is_sum_sq(red)) {
+      for (uint32_t c = lane; c < S.chunks_per_block; c += 64) acc += (double)partials[first + c];
+      acc = am_wave_sum_f64(acc);
+    } else {
+      for (uint32_t c = lane; c < S.chunks_per_block; c += 64) acc = am_combine(red, acc, (double)partials[first + c]);
+      acc = am_wave_reduce_f64(red, acc);
+    }
     if (lane == 0) {
       const uint64_t v_idx = S.v_first + block;
       float v_new, scale;
-      am_block_scalars((float)acc, (float)S.block_numel, v[v_idx], sc, &v_new, &scale);
+      am_block_scalars(am_red_finish(red, (float)acc, (float)S.block_numel), v[v_idx], sc, &v_new, &scale);
       v[v_idx] = v_new;
       scales[lb] = scale;
     }
@@ -518,9 +566,10 @@ __global__ __launch_bounds__(kStridedThreads) void am_strided_partial(AM_KERNEL_
     const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
     const AmSeg& S = *it.seg;
     const uint64_t rows = S.block_numel, row_len = S.row_len;
+    const uint32_t red = S.reducer;
     float acc[VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
+    for (int j = 0; j < VEC; ++j) acc[j] = am_red_identity(red);
     for (int r = 0; r < kStridedRows; r += kStridedUnroll) {
       float gv[kStridedUnroll][VEC];
 #pragma unroll
@@ -533,10 +582,22 @@ __global__ __launch_bounds__(kStridedThreads) void am_strided_partial(AM_KERNEL_
           for (int j = 0; j < VEC; ++j) gv[q][j] = 0.0f;
         }
       }
+      if (am_red_is_sum_sq(red)) {
 #pragma unroll
-      for (int q = 0; q < kStridedUnroll; ++q)
+        for (int q = 0; q < kStridedUnroll; ++q)
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) acc[j] = fmaf(gv[q][j], gv[q][j], acc[j]);
+          for (int j = 0; j < VEC; ++j) acc[j] = fmaf(gv[q][j], gv[q][j], acc[j]);
+      } else {
+#pragma unroll
+        for (int q = 0; q < kStridedUnroll; ++q)
+          if (it.lane_on && it.row0 + r + q < rows) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+              const float one[1] = {gv[q][j]};  // a lane's VEC columns are VEC different blocks
+              acc[j] = am_red_accumulate(red, one, acc[j]);
+            }
+          }
+      }
     }
     // plain (cached) stores: the finalize kernel reads these back right away
     if (it.lane_on) {
@@ -558,11 +619,16 @@ __global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uin
     const uint64_t col = gc - lblock_keys[s];
     const uint64_t rows = S.block_numel, row_len = S.row_len;
     const uint64_t n_chunks = (rows + kStridedRows - 1) / kStridedRows;
-    double acc = 0.0;
-    for (uint64_t c = 0; c < n_chunks; ++c) acc += (double)partials[S.aux + c * row_len + col];
+    const uint32_t red = S.reducer;
+    double acc = (double)am_red_identity(red);
+    if (am_red_is_sum_sq(red)) {
+      for (uint64_t c = 0; c < n_chunks; ++c) acc += (double)partials[S.aux + c * row_len + col];
+    } else {
+      for (uint64_t c = 0; c < n_chunks; ++c) acc = am_combine(red, acc, (double)partials[S.aux + c * row_len + col]);
+    }
     const uint64_t v_idx = S.v_first + col;
     float v_new, scale;
-    am_block_scalars((float)acc, (float)rows, v[v_idx], sc, &v_new, &scale);
+    am_block_scalars(am_red_finish(red, (float)acc, (float)rows), v[v_idx], sc, &v_new, &scale);
     v[v_idx] = v_new;
     scales[gc] = scale;
   }
@@ -676,7 +742,8 @@ __global__ __launch_bounds__(THREADS) void am_elementwise(AM_KERNEL_PARAMS,
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
           float v_new, scale;
-          am_block_scalars(gv[k][j] * gv[k][j], 1.0f, vv[k][j], sc, &v_new, &scale);
+          // a block of one element: every statistic of the 1-vector g*g is g*g itself
+          am_block_scalars(gv[k][j] * gv[k][j], vv[k][j], sc, &v_new, &scale);
           vv[k][j] = v_new;
           am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale, decay, sc);
         }

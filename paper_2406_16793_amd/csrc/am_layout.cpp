@@ -108,6 +108,7 @@ AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel
   var.lanes = 256;
   var.upt = (t.large_chunk_upt == 1 || t.large_chunk_upt == 2 || t.large_chunk_upt == 8 || t.large_chunk_upt == 16)
                 ? (int)t.large_chunk_upt : 4;
+  if (var.vec * var.upt > 64) var.upt = 64 / var.vec;  // the partial-sum kernel holds a chunk's gradient in registers
   return var;
 }
 
@@ -123,7 +124,8 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
   for (uint32_t k = 0; k < n_tensors; ++k) {
     const adam_mini_tensor_desc& d = descs[k];
     if (d.numel == 0 || d.block_numel == 0 || d.numel % d.block_numel != 0) return ADAM_MINI_INVALID_ARG;
-    if ((d.flags & ~(uint32_t)ADAM_MINI_FLAG_STRIDED) != 0) return ADAM_MINI_INVALID_ARG;
+    if ((d.flags & ~(uint32_t)(ADAM_MINI_FLAG_STRIDED | ADAM_MINI_REDUCE_MASK)) != 0) return ADAM_MINI_INVALID_ARG;
+    if ((d.flags & ADAM_MINI_REDUCE_MASK) > ADAM_MINI_REDUCE_MIN) return ADAM_MINI_INVALID_ARG;
     if (!std::isfinite(d.wd_scale) || d.wd_scale < 0.0f) return ADAM_MINI_INVALID_ARG;
     if (d.numel >= (1ull << 48)) return ADAM_MINI_INVALID_ARG;  // keeps every product below in 64 bits
     AmTensorInfo ti{};
@@ -170,6 +172,8 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     s.lblock_first = (uint32_t)bk.n_lblocks;
     s.tensor = k;
     s.wd_scale = d.wd_scale;
+    s.reducer = (d.flags & ADAM_MINI_REDUCE_MASK) >> 4;  // same numbering as the kernels' AM_RED_*
+    if ((d.flags & ADAM_MINI_REDUCE_MASK) > ADAM_MINI_REDUCE_NORM1) bk.alt_reducer = true;
     uint64_t items = 0;
     if (var.family == AM_FAM_ELEMENTWISE) {
       s.block_numel = d.numel;

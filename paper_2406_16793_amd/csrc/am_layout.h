@@ -30,6 +30,7 @@ struct AmBucket {
   uint64_t n_partials = 0;  // STRIDED: floats of partial sums the bucket needs
   uint64_t table_offset = 0;  // index of segs[0] in the concatenated device table
   uint64_t lds_bytes = 0;     // ROW_LDS: bytes of LDS that hold the largest block's gradient
+  bool alt_reducer = false;   // some tensor's block statistic is not a plain sum of squares (2-norm, max, min)
 };
 
 // Knobs of the variant choice (process-wide defaults; copied into a layout when it is built).

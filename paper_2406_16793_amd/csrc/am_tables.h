@@ -31,7 +31,7 @@ struct AmSeg {
   uint32_t chunks_per_block; // LARGE: work items per block; otherwise 1
   uint32_t tensor;        // index in the caller's tensor list
   float wd_scale;         // lambda_k = weight_decay * wd_scale
-  uint32_t pad_;
+  uint32_t reducer;       // block statistic of g .* g that feeds v: 0 mean (the method), 1 1-norm, 2 2-norm, 3 max, 4 min
   uint64_t aux;           // STRIDED: index of the tensor's first partial sum in the scratch
   uint64_t row_len;       // STRIDED: elements per stored row (= number of blocks C)
 };

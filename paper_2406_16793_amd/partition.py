@@ -31,6 +31,8 @@ class TensorSpec:
     block_numel: int
     wd_scale: float = 1.0
     strided: bool = False   # blocks are the COLUMNS of the stored [block_numel, n_blocks] matrix (weight kept transposed)
+    reducer: str = "mean"   # block statistic of g*g that feeds v: "mean" (the method), or the appendix
+                            # ablation's "norm1", "norm2", "max", "min"
 
     @property
     def numel(self) -> int:
@@ -119,10 +121,19 @@ def as_adamw(specs: Sequence[TensorSpec]) -> List[TensorSpec]:
     return [TensorSpec(s.name, s.shape, 1, s.wd_scale) for s in specs]
 
 
+def with_reducer(specs: Sequence[TensorSpec], reducer: str) -> List[TensorSpec]:
+    """The same partition with another block statistic in the v update (the candidates of the
+    paper's "Ablation Studies on the Design of Adam-mini": 1-norm, 2-norm, max, min of g*g)."""
+    if reducer not in ("mean", "norm1", "norm2", "max", "min"):
+        raise ValueError("unknown reducer %r" % (reducer,))
+    return [TensorSpec(s.name, s.shape, s.block_numel, s.wd_scale, s.strided, reducer) for s in specs]
+
+
 def transposed(spec: TensorSpec) -> TensorSpec:
     """The same 2-D weight and the same blocks, stored as the transpose: a [rows, cols] tensor cut
     by rows becomes a [cols, rows] tensor whose blocks are its columns (the re-ordering case of the
     paper's Appendix D).  Only for tensors partitioned by their outermost dimension's rows."""
     if len(spec.shape) != 2 or spec.strided or spec.block_numel != spec.shape[1]:
         raise ValueError("transposed() needs a 2-D tensor partitioned by rows")
-    return TensorSpec(spec.name + ".T", (spec.shape[1], spec.shape[0]), spec.block_numel, spec.wd_scale, True)
+    return TensorSpec(spec.name + ".T", (spec.shape[1], spec.shape[0]), spec.block_numel, spec.wd_scale, True,
+                      spec.reducer)

@@ -65,7 +65,8 @@ def run_both(wl: workloads.Workload, steps=None, hp=None, mutate_grad=None, chec
         run.p[k].copy_(x)
         p0.append(x.cpu().numpy())
     st = orc.OracleState([s.numel for s in wl.specs], [s.block_numel for s in wl.specs],
-                         [s.wd_scale for s in wl.specs], p0, strided=[s.strided for s in wl.specs])
+                         [s.wd_scale for s in wl.specs], p0, strided=[s.strided for s in wl.specs],
+                         reducer=[s.reducer for s in wl.specs])
     hp = hp or dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
     ohp = orc.Hyper.from_f32(**hp)
     worst = 0.0
@@ -153,7 +154,8 @@ def run_sampled(wl: workloads.Workload, steps=None, per_tensor=6, large_per_tens
         if k in active:
             p0.append(gather(run.p, k).cpu().numpy().reshape(-1))
     st = orc.OracleState([len(picks[k]) * wl.specs[k].block_numel for k in active],
-                         [wl.specs[k].block_numel for k in active], [wl.specs[k].wd_scale for k in active], p0)
+                         [wl.specs[k].block_numel for k in active], [wl.specs[k].wd_scale for k in active], p0,
+                         reducer=[wl.specs[k].reducer for k in active])
     hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
     ohp = orc.Hyper.from_f32(**hp)
     for t in range(1, steps + 1):

@@ -250,3 +250,14 @@ def test_random_layouts_against_oracle(oracle):
         assert sum(b["numel"] for b in infos) == sum(numel)
         assert sum(b["n_blocks"] for b in infos) == B.adam_mini_num_blocks(h)
         B.adam_mini_destroy_layout(h)
+
+
+def test_reducer_flags_are_validated():
+    """Bits 4-6 of the descriptor flags select the block statistic; codes above MIN and other bits are rejected."""
+    for name, flag in B.REDUCE_FLAGS.items():
+        h = B.adam_mini_init_layout([(4096 * 4, 4096, 1.0, flag), (64, 8, 1.0, flag | B.FLAG_STRIDED)], B.GRAD_BF16, -1)
+        assert B.adam_mini_num_blocks(h) == 4 + 8, name
+        B.adam_mini_destroy_layout(h)
+    for bad in (5 << 4, 7 << 4, 1 << 7, 1 << 1, 1 << 3):
+        with pytest.raises(B.AdamMiniError):
+            B.adam_mini_init_layout([(4096, 4096, 1.0, bad)], B.GRAD_F32, -1)

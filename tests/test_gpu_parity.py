@@ -287,6 +287,67 @@ def test_step_can_be_captured_in_a_hip_graph():
         run.close()
 
 
+REDUCER_SHAPES = (ROW_SHAPES[:13] + ODD_SHAPES[:7] + LARGE_SHAPES[:3] + [(2, 32768), (1, 36000)] + ADAMW_SHAPES[:2])
+
+
+def _reducer_specs(reducers):
+    """Every kernel family (register teams of each size, LDS-staged, multi-workgroup, column blocks,
+    one-element blocks); tensor i takes reducers[i % len(reducers)]."""
+    import gpu_harness as H
+    from paper_2406_16793_amd.partition import TensorSpec
+    specs = H.make_specs(REDUCER_SHAPES) + H.make_specs(STRIDED_SHAPES[:6], strided=True)
+    return [TensorSpec(s.name, s.shape, s.block_numel, s.wd_scale, s.strided, reducers[i % len(reducers)])
+            for i, s in enumerate(specs)]
+
+
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("reducer", ["norm1", "norm2", "max", "min", "mixed"])
+def test_alternative_block_statistics(reducer, grad_dtype):
+    """The ablation's candidates for the block statistic (appendix, "Ablation Studies on the Design of
+    Adam-mini"): r(g*g) with r = 1-norm, 2-norm, max, min in the v line of Algorithm 1, against the
+    oracle's statement of the same reading.  "mixed" gives neighbouring tensors different statistics,
+    so 16-lane teams of one wavefront differ."""
+    import gpu_harness as H
+    from paper_2406_16793_amd import workloads
+    reducers = ["mean", "max", "norm2", "min", "norm1"] if reducer == "mixed" else [reducer]
+    specs = _reducer_specs(reducers)
+    rtol = 5e-3 if grad_dtype == "bf16" else 1e-5
+    wl = workloads.Workload("reducers", 94, specs, grad_dtype, 3, rtol=rtol, zero_row_prob=0.2, zero_row_tensors=(3, 9))
+    run, st, worst = H.run_both(wl, check_every_step=True)
+    print("%s: worst normwise rel err %.3g" % (reducer, worst), flush=True)
+    assert worst < 1e-5
+    run.close()
+
+
+@pytest.mark.parametrize("reducer", ["norm1", "norm2", "max", "min"])
+def test_alternative_statistics_hand_a_nan_on(reducer):
+    import gpu_harness as H
+    from paper_2406_16793_amd import workloads
+    from paper_2406_16793_amd.partition import with_reducer
+    shapes = [(4, 4096), (2, 49152), (3, 64), (5, 8)]
+    specs = with_reducer(H.make_specs(shapes) + H.make_specs([(1024, 16)], strided=True), reducer)
+    wl = workloads.Workload("reducers_nan", 95, specs, "f32", 2)
+
+    def poison(k, t, g):
+        if t == 1 and k == 0:
+            g[4096 + 17] = float("nan")     # block 1 of tensor 0
+        if t == 1 and k == 1:
+            g[49152 + 5] = float("nan")     # block 1 of tensor 1
+        if t == 1 and k == 2:
+            g[64 + 63] = float("inf")       # block 1 of tensor 2
+        if t == 1 and k == 3:
+            g[2 * 8] = float("nan")         # block 2 of tensor 3
+        if t == 1 and k == 4:
+            g[7 * 1024 + 5] = float("nan")  # row 7, column 5 of the stored [16, 1024] matrix
+    run, st, _ = H.run_both(wl, mutate_grad=poison, check_every_step=True)
+    p0 = run.p[0].cpu().numpy().reshape(4, 4096)
+    assert np.isnan(p0[1]).all() and np.isfinite(p0[[0, 2, 3]]).all()
+    v = run.v.cpu().numpy()
+    assert np.isnan(v[1]) and np.isnan(v[4 + 1]) and np.isnan(v[4 + 2 + 3 + 2]) and np.isnan(v[4 + 2 + 3 + 5 + 5])
+    assert np.isnan(v).sum() == 4
+    run.close()
+
+
 # enough work items per family for several whole spans of 8 * chunk workgroup passes and a ragged tail
 SWIZZLE_SHAPES = [(1500, 64), (1100, 256), (300, 4096), (70, 11008), (3, 200000), (300001, 1), (5, 36000)]
 
