@@ -65,3 +65,58 @@ def test_full_size_adamw_equivalent_mode():
     run.close()
     del run
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("kind", ["rows", "adamw", "columns"])
+def test_tensor_beyond_2_to_32_elements(kind):
+    """One tensor of more than 2^32 elements (17 GB of fp32 parameters): element offsets are 64-bit in every
+    kernel family that can hold such a tensor.  The sample always holds the first and the last block, the
+    last one lying wholly above element 2^32."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import workloads
+    from paper_2406_16793_amd.partition import TensorSpec
+    if kind == "rows":
+        big = TensorSpec("huge.weight", (524293, 8192), 8192)           # 2^32 + 5 rows of 8192
+    elif kind == "adamw":
+        big = TensorSpec("huge.weight", (524293, 8192), 1)              # dense v of the same size
+    else:
+        big = TensorSpec("huge.weight.T", (8192, 524292), 8192, 1.0, True)   # column blocks, 2^32 + 4 columns
+    assert big.numel > 2 ** 32
+    specs = [TensorSpec("small.weight", (7, 4096), 4096), big, TensorSpec("tail.weight", (3, 256), 256)]
+    wl = workloads.Workload("huge_" + kind, 96, specs, "bf16", 2, rtol=5e-3)
+    need = big.numel * (14 if kind == "adamw" else 10) + (24 << 30)      # + the fp32 slab of the gradient generator
+    if torch.cuda.get_device_properties(0).total_memory < need:
+        pytest.skip("needs %.0f GB of device memory" % (need / 1e9))
+    _say("%s: %d elements in one tensor" % (wl.name, big.numel))
+    run, worst = H.run_sampled(wl, steps=2, progress=_say)
+    _say("%s: worst normwise rel err over sampled blocks %.3g" % (wl.name, worst))
+    assert worst < 1e-5
+    assert bool(torch.isfinite(run.p[1][-8192:]).all()) and float(run.m[1][-8192:].abs().max()) > 0.0
+    run.close()
+    del run
+    torch.cuda.empty_cache()
+
+
+def test_full_size_alternative_block_statistics():
+    """Llama-2-7B shape with the ablation's block statistics spread over the tensors (tensor k takes
+    statistic k mod 5, so every kernel family meets every statistic): sampled blocks against the oracle."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import workloads
+    from paper_2406_16793_amd.partition import TensorSpec
+    wl = workloads.get("llama2_7b")
+    names = ["max", "norm2", "mean", "min", "norm1"]
+    wl.specs = [TensorSpec(s.name, s.shape, s.block_numel, s.wd_scale, s.strided, names[k % 5])
+                for k, s in enumerate(wl.specs)]
+    wl.name = "llama2_7b_statistics"
+    need = wl.n_params * 10 + (6 << 30)
+    if torch.cuda.get_device_properties(0).total_memory < need:
+        pytest.skip("needs %.0f GB of device memory" % (need / 1e9))
+    run, worst = H.run_sampled(wl, steps=3, progress=_say)
+    _say("%s: worst normwise rel err over sampled blocks %.3g" % (wl.name, worst))
+    assert worst < 1e-5
+    assert bool(torch.isfinite(run.v).all()) and float(run.v.min()) >= 0.0
+    run.close()
+    del run
+    torch.cuda.empty_cache()
