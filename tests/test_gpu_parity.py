@@ -194,6 +194,39 @@ def test_pointer_lists_may_change_between_steps():
     run.close()
 
 
+def test_two_layouts_step_concurrently_on_two_streams():
+    """Each layout owns its tables and scratch, so two optimizers may run at the same time on different
+    streams (default priority): the bits equal those of running them one after the other."""
+    import gpu_harness as H
+    import torch
+    shapes_a = [(300, 4096), (3, 49152), (2, 200000), (5000, 1)]
+    shapes_b = [(2, 524288), (64, 11008), (1000, 64)]
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    results = []
+    for concurrent in (False, True):
+        torch.manual_seed(11)
+        runs = [H.GpuRun(H.make_specs(sh) + (H.make_specs([(512, 96)], strided=True) if i == 0 else []), "bf16")
+                for i, sh in enumerate((shapes_a, shapes_b))]
+        for run in runs:
+            for k, s in enumerate(run.specs):
+                run.p[k].copy_(torch.randn(s.numel) * 0.02)
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()] if concurrent else [torch.cuda.current_stream()] * 2
+        for t in range(1, 5):
+            for run in runs:
+                for k, s in enumerate(run.specs):
+                    run.g[k].copy_((torch.randn(s.numel) * 1e-3).to(torch.bfloat16))
+            torch.cuda.synchronize()
+            for run, st in zip(runs, streams):
+                run.opt.step(step=t, stream=st.cuda_stream, **hp)
+            torch.cuda.synchronize()
+        results.append([[x.clone() for x in run.p + run.m] + [run.v.clone()] for run in runs])
+        for run in runs:
+            run.close()
+    for a, b in zip(results[0], results[1]):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+
+
 def test_misaligned_pointer_is_rejected_on_the_gpu_too():
     import gpu_harness as H
     import torch
