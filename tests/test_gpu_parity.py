@@ -295,6 +295,7 @@ def test_step_can_be_captured_in_a_hip_graph():
     runs = []
     for _ in range(2):
         wl = _wl(shapes, "bf16", steps=3)
+        wl.specs = wl.specs + H.make_specs([(512, 96)], strided=True)      # column blocks: three more kernels
         run = H.GpuRun(wl.specs, "bf16")
         torch.manual_seed(5)
         for k, s in enumerate(wl.specs):
