@@ -419,6 +419,25 @@ def test_xcd_swizzle_visits_every_item_once_and_keeps_the_bits(oracle):
         B.adam_mini_set_option("reset", 0)
 
 
+def test_thousands_of_small_tensors():
+    """2500 tensors of a few blocks each (adapter- and bias-sized): workgroups whose 16-lane teams fall
+    on different tensors, deep table walks, every small-team variant."""
+    import gpu_harness as H
+    from paper_2406_16793_amd import workloads
+    from paper_2406_16793_amd.partition import TensorSpec
+    rng = np.random.default_rng(2500)
+    specs = []
+    for i in range(2500):
+        bn = int(rng.choice([1, 3, 8, 16, 24, 64, 100, 128, 256, 384, 768, 1024]))
+        nb = int(rng.integers(1, 9))
+        specs.append(TensorSpec("small%d.weight" % i, (nb, bn), bn, float(rng.choice([0.0, 1.0]))))
+    wl = workloads.Workload("small_tensors", 97, specs, "bf16", 2, rtol=5e-3)
+    run, st, worst = H.run_both(wl)
+    print("2500 tensors: worst normwise rel err %.3g" % worst, flush=True)
+    assert worst < 1e-5
+    run.close()
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3, 4])
 def test_random_layouts(seed, oracle):
     """Seeded random tensor lists mixing every family, both layouts, odd sizes: parity and block ids."""
