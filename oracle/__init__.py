@@ -207,7 +207,14 @@ class OracleState:
     def __init__(self, numel: Sequence[int], block_numel: Sequence[int],
                  wd_scale: Optional[Sequence[float]], params0: Sequence[np.ndarray],
                  lib: Optional[OracleLib] = None, strided: Optional[Sequence[bool]] = None,
-                 reducer: Optional[Sequence[str]] = None):
+                 reducer: Optional[Sequence[str]] = None, storage: str = "f64"):
+        """storage = "f64": the state stays in double between steps (the reference the tolerances are
+        stated against).  storage = "f32": p, m and v are rounded to fp32 after every step, as a
+        library that stores them in fp32 must; comparing against both tells storage rounding from
+        arithmetic error when a parity failure is being diagnosed."""
+        if storage not in ("f64", "f32"):
+            raise ValueError("storage must be 'f64' or 'f32'")
+        self.storage = storage
         self.lib = lib or default_lib()
         self.reducer = ["mean"] * len(numel) if reducer is None else [str(x) for x in reducer]
         self.strided = [False] * len(numel) if strided is None else [bool(x) for x in strided]
@@ -229,6 +236,10 @@ class OracleState:
             self.lib.step_tensor(self.p[k], self.m[k], self.v[k], np.ascontiguousarray(g).reshape(-1),
                                  self.block_numel[k], hp, self.t, self.wd_scale[k], self.strided[k],
                                  self.reducer[k])
+            if self.storage == "f32":
+                with np.errstate(over="ignore"):
+                    for a in (self.p[k], self.m[k], self.v[k]):
+                        a[:] = a.astype(np.float32).astype(np.float64)
 
     def v_flat(self) -> np.ndarray:
         return np.concatenate(self.v) if self.v else np.zeros(0)

@@ -52,7 +52,7 @@ def make_specs(blocks, strided=False):
 
 
 def run_both(wl: workloads.Workload, steps=None, hp=None, mutate_grad=None, check_every_step=False,
-             gen_device="cpu"):
+             gen_device="cpu", storage="f64"):
     """Steps the HIP library and the oracle over the whole workload `wl` with the same
     inputs and compares p, m and v after the last step (or after every step).
     Returns (GpuRun, OracleState, worst normwise relative error)."""
@@ -66,7 +66,7 @@ def run_both(wl: workloads.Workload, steps=None, hp=None, mutate_grad=None, chec
         p0.append(x.cpu().numpy())
     st = orc.OracleState([s.numel for s in wl.specs], [s.block_numel for s in wl.specs],
                          [s.wd_scale for s in wl.specs], p0, strided=[s.strided for s in wl.specs],
-                         reducer=[s.reducer for s in wl.specs])
+                         reducer=[s.reducer for s in wl.specs], storage=storage)
     hp = hp or dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
     ohp = orc.Hyper.from_f32(**hp)
     worst = 0.0

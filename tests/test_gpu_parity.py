@@ -91,6 +91,22 @@ def test_config1_tiny_10_steps():
     run.close()
 
 
+def test_error_splits_into_storage_rounding_and_arithmetic():
+    """The same run against the oracle's two state modes: fp64 state (the contract) and state rounded to fp32
+    after every step (what any fp32-state library must do).  Both stay far inside the tolerance; the second
+    shows how much of the distance is storage rounding."""
+    import gpu_harness as H
+    from paper_2406_16793_amd import workloads
+    errs = {}
+    for storage in ("f64", "f32"):
+        run, st, worst = H.run_both(workloads.get("tiny"), storage=storage)
+        errs[storage] = worst
+        run.close()
+    print("normwise rel err after 10 steps: vs fp64-state oracle %.3g, vs fp32-storage oracle %.3g"
+          % (errs["f64"], errs["f32"]), flush=True)
+    assert errs["f64"] < 1e-5 and errs["f32"] < 1e-5
+
+
 def test_config2_gpt2_small_20_steps():
     import gpu_harness as H
     from paper_2406_16793_amd import workloads
