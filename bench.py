@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--reducer", default="mean", choices=["mean", "norm1", "norm2", "max", "min"],
                     help="block statistic of g*g in the v update (mean = the method; the others are the ablation's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other BASELINE configurations (reported under all_configs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
@@ -193,7 +195,52 @@ def main():
     else:
         out["cpu_baseline"] = None
     run.close()
+    del run
+    default_run = args.workload == "llama2_7b" and not args.adamw and args.reducer == "mean" and not args.option
+    if default_run and not args.no_other_configs:
+        out["all_configs"] = other_configs(out, torch, B, workloads, DeviceState)
     print(json.dumps(out), flush=True)
+
+
+def other_configs(primary, torch, B, workloads, DeviceState):
+    """Throughput and HBM fraction of every BASELINE configuration on this GPU: the timed workload above plus a
+    short run (2 warm-up + 5 timed steps) of each of the others that fits the device, same launch configuration."""
+    rows = [{"workload": primary["config"]["workload"], "ms_per_step": primary["ms_per_step"],
+             "Gparams_per_s": primary["value"], "algorithmic_GBps": primary["whole_step"]["algorithmic_GBps"],
+             "frac_of_peak": primary["whole_step"]["frac_of_peak"]}]
+    total_mem = torch.cuda.get_device_properties(0).total_memory
+    for name in ("tiny", "gpt2_small", "llama3_8b", "llama2_13b"):
+        wl = workloads.get(name)
+        gb = 2 if wl.grad_dtype == "bf16" else 4
+        n_params = sum(s.numel for s in wl.specs)
+        if n_params * (8 + gb + 4) + (8 << 30) > total_mem:
+            rows.append({"workload": name, "skipped": "does not fit this device"})
+            continue
+        torch.cuda.empty_cache()
+        run = DeviceState(wl.specs, wl.grad_dtype)
+        for k, s in enumerate(wl.specs):
+            run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
+            workloads.fill_grad(run.g[k], s, wl, k, 1, row_chunk=8192)
+        hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
+        stream = torch.cuda.current_stream().cuda_stream
+        t, steps = 0, (200 if name == "tiny" else 5)
+        for _ in range(2):
+            t += 1
+            run.opt.step(step=t, stream=stream, **hp)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            t += 1
+            run.opt.step(step=t, stream=stream, **hp)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        gbs = (n_params * (16 + gb) + 8 * run.opt.num_blocks) / (ms * 1e-3) / 1e9
+        rows.append({"workload": name, "ms_per_step": round(ms, 4), "Gparams_per_s": round(n_params / ms / 1e6, 2),
+                     "algorithmic_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)})
+        run.close()
+        del run
+    torch.cuda.empty_cache()
+    return rows
 
 
 if __name__ == "__main__":
