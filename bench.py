@@ -86,6 +86,7 @@ def cpu_baseline(wl, run, hp, target_seconds):
 
     cores = orc.num_threads()
     orc.set_num_threads(1)
+    _progress("cpu baseline: oracle on %d tensors" % len(specs))
     steps1, spent1 = timed(0.2 * target_seconds)          # one host thread
     orc.set_num_threads(cores)
     steps, spent = timed(0.8 * target_seconds)            # one thread per host core
@@ -94,6 +95,12 @@ def cpu_baseline(wl, run, hp, target_seconds):
             "sample": "%d tensors of layer 0 (%d params, %d blocks); %d oracle steps in %.1f s on %d threads, "
                       "%d steps in %.1f s on 1 thread"
                       % (len(specs), n, sum(s.n_blocks for s in specs), steps, spent, cores, steps1, spent1)}
+
+
+def _progress(msg):
+    """One line per stage on stderr (stdout carries only the JSON line)."""
+    sys.stderr.write("[bench] %s\n" % msg)
+    sys.stderr.flush()
 
 
 def main():
@@ -121,11 +128,16 @@ def main():
     hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
 
     torch.cuda.set_device(0)
+    _progress("%s: %d tensors, allocating" % (wl.name, len(wl.specs)))
     run = DeviceState(wl.specs, wl.grad_dtype)
     for k, s in enumerate(wl.specs):
         run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
         workloads.fill_grad(run.g[k], s, wl, k, 1, row_chunk=8192)
+        if k % 64 == 63:
+            torch.cuda.synchronize()
+            _progress("inputs of %d tensors ready" % (k + 1))
     torch.cuda.synchronize()
+    _progress("inputs ready")
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=run.dev)   # 1 GiB
@@ -141,6 +153,7 @@ def main():
         t += 1
         run.opt.step(step=t, stream=stream, **hp)
     torch.cuda.synchronize()
+    _progress("%d warm-up steps done" % args.warmup)
     B.adam_mini_profile_enable(run.opt.layout, args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -149,6 +162,7 @@ def main():
         run.opt.step(step=t, stream=stream, **hp)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    _progress("%d timed steps done" % args.steps)
     buckets = B.adam_mini_profile_read(run.opt.layout)
     B.adam_mini_profile_enable(run.opt.layout, 0)
 
@@ -217,6 +231,7 @@ def other_configs(primary, torch, B, workloads, DeviceState):
             rows.append({"workload": name, "skipped": "does not fit this device"})
             continue
         torch.cuda.empty_cache()
+        _progress("all_configs: %s" % name)
         run = DeviceState(wl.specs, wl.grad_dtype)
         for k, s in enumerate(wl.specs):
             run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
