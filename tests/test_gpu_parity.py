@@ -186,6 +186,44 @@ def test_eps_zero_and_extreme_hyperparameters():
         run.close()
 
 
+def test_resume_at_a_late_step():
+    """State handed over from a checkpoint: m and v are not zero and t starts at 10^6 (bias corrections ~ 1,
+    beta^t underflows) and at 12 (bias corrections far from 1)."""
+    import gpu_harness as H
+    import torch
+    import oracle as orc
+    shapes = [(40, 4096), (2, 49152), (3, 100000), (300, 1), (7, 333)]
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    for t0 in (1_000_000, 12):
+        wl = _wl(shapes, "bf16", steps=3)
+        run = H.GpuRun(wl.specs, "bf16")
+        torch.manual_seed(t0)
+        p0 = [torch.randn(s.numel) * 0.02 for s in wl.specs]
+        m0 = [torch.randn(s.numel) * 1e-3 for s in wl.specs]
+        v0 = torch.rand(run.opt.num_blocks) * 1e-6 + 1e-9
+        st = orc.OracleState([s.numel for s in wl.specs], [s.block_numel for s in wl.specs],
+                             [s.wd_scale for s in wl.specs], [x.numpy() for x in p0])
+        off = 0
+        for k, s in enumerate(wl.specs):
+            run.p[k].copy_(p0[k])
+            run.m[k].copy_(m0[k])
+            st.m[k][:] = m0[k].numpy()
+            st.v[k][:] = v0[off:off + s.n_blocks].numpy()
+            off += s.n_blocks
+        run.v.copy_(v0)
+        st.t = t0 - 1
+        for t in range(t0, t0 + 3):
+            g = [(torch.randn(s.numel) * 1e-3).to(torch.bfloat16) for s in wl.specs]
+            for k in range(len(g)):
+                run.g[k].copy_(g[k])
+            run.opt.step(step=t, **hp)
+            st.step([H.grad_to_host(x) for x in g], orc.Hyper.from_f32(**hp))
+        torch.cuda.synchronize()
+        worst = H.compare(run, st, 5e-3, label="t0=%d" % t0)
+        assert worst < 1e-5, (t0, worst)
+        run.close()
+
+
 def test_pointer_lists_may_change_between_steps():
     """New gradient buffers every step (as a framework that reallocates .grad would pass them)."""
     import gpu_harness as H
