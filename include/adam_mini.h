@@ -12,7 +12,7 @@
  *     v_b     <- (1 - beta2) * (sum_i g_i^2) / n_b + beta2 * v_b   (ONE scalar per block)
  *     param_i <- param_i - (lr / bc1) * m_i / (sqrt(v_b / bc2) + eps)
  *
- * The partition (Algorithm 3, "Partition for Transformers", Appendix B: embedding
+ * The partition (listing "Partition for Transformers", Appendix B: embedding
  * and output layers by token, query/key by head, value / attention projection /
  * MLP by output neuron, everything else as one block) always cuts a row-major
  * tensor whose partition dimension is outermost into equal, contiguous runs of
@@ -42,8 +42,9 @@ extern "C" {
 typedef enum adam_mini_status {
   ADAM_MINI_OK = 0,
   ADAM_MINI_INVALID_ARG = -1,   /* null pointer, zero size, block_numel does not divide numel,
-                                   flags != 0, step == 0, beta outside [0,1), eps < 0,
-                                   non-finite hyper-parameter, unknown dtype, bad tensor index */
+                                   a reserved flag bit or an unknown ADAM_MINI_REDUCE_* value, step == 0,
+                                   beta outside [0,1), eps < 0, non-finite hyper-parameter, unknown dtype,
+                                   bad tensor index, a size beyond a documented limit */
   ADAM_MINI_MISALIGNED = -2,    /* a device base pointer is not 16-byte aligned */
   ADAM_MINI_OUT_OF_MEMORY = -3, /* host or device allocation failed */
   ADAM_MINI_HIP_ERROR = -4,     /* a HIP runtime call failed (see adam_mini_last_hip_error) */
@@ -117,7 +118,7 @@ typedef struct adam_mini_hparams {
 typedef struct adam_mini_layout adam_mini_layout; /* opaque */
 
 /*
- * Build the block layout of a tensor list (Algorithm 3 realised as descriptors).
+ * Build the block layout of a tensor list ("Partition for Transformers", Appendix B, realised as descriptors).
  * Host-only work: validates the descriptors, assigns v indices (the v scalars of
  * all tensors are stored back to back in tensor order: tensor k owns
  * v[v_offset[k] .. v_offset[k+1]), v_offset = exclusive prefix sum of

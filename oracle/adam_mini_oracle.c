@@ -10,22 +10,27 @@
  * widened exactly.  Hyper-parameters arrive as doubles (the caller widens the
  * same fp32 values the GPU library receives).
  *
- * Source of each formula: the paper's Algorithm 1 ("Adam-mini, general form",
- * Section 2.3) which is repeated as Algorithm 2 in Appendix B.  Per block:
- *     g      = grad of the block
- *     param  = param - lr * lambda * param
- *     m      = (1 - beta1) * g + beta1 * m
- *     m_hat  = m / (1 - beta1^t)
- *     v      = (1 - beta2) * mean(g .* g) + beta2 * v      (one scalar per block)
+ * What is computed is Algorithm 1 ("Adam-mini, general form", Section 2.3; the
+ * same update again in PyTorch style as Algorithm 2, Appendix B).  With g the
+ * block's gradient, n its size and t >= 1 the step, this file evaluates it as
+ *     stat   = (1/n) * sum_i g_i^2                  the block's mean squared gradient
+ *     v      = (1 - beta2) * stat + beta2 * v       ONE second moment per block
  *     v_hat  = v / (1 - beta2^t)
- *     param  = param - lr * m_hat / (sqrt(v_hat) + eps)
+ *   and then for every element i of the block
+ *     param_i = param_i - lr * lambda * param_i     decoupled weight decay
+ *     m_i     = (1 - beta1) * g_i + beta1 * m_i
+ *     m_hat   = m_i / (1 - beta1^t)
+ *     param_i = param_i - lr * m_hat / (sqrt(v_hat) + eps)
+ * The statistic comes first only because everything after it needs it; each
+ * element still sees decay, first moment and step in Algorithm 1's order.
  * The blocks of one tensor are the consecutive, equally sized, contiguous runs
  * of `block_numel` elements of the row-major tensor: that is what "partition
- * by tokens / heads / output neurons" (Algorithm 3, Appendix B) yields when the
+ * by tokens / heads / output neurons" (listing "Partition for Transformers",
+ * Appendix B) yields when the
  * partition dimension is the outermost one.  When a codebase stores the weight
  * transposed (Appendix D notes that re-ordering is then needed) the same blocks
  * are the COLUMNS of the stored matrix: the `strided` form below.  block_numel == 1 is vanilla AdamW
- * (Section 2.3, "replaces g.*g in vanilla Adam by its mean value"); block_numel
+ * (Section 2.3: the method is Adam with g .* g replaced by its block mean); block_numel
  * == numel is the non-Transformer partition (Algorithm "Partition for
  * non-Transformers", Appendix B).
  *
@@ -89,17 +94,7 @@ void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
   double bias1 = 1.0 - pow(beta1, (double)t);
   double bias2 = 1.0 - pow(beta2, (double)t);
 
-  /* param = param - lr * lambda * param */
-  for (uint64_t i = 0; i < n; ++i)
-    p[i * stride] = p[i * stride] - lr * lambda * p[i * stride];
-
-  /* m = (1 - beta1) * g + beta1 * m */
-  for (uint64_t i = 0; i < n; ++i) {
-    double gi = amo_grad_at(g, dtype, g_first + i * stride);
-    m[i * stride] = (1.0 - beta1) * gi + beta1 * m[i * stride];
-  }
-
-  /* v = (1 - beta2) * mean(g .* g) + beta2 * v : one scalar for the block */
+  /* the block statistic of Algorithm 1: the mean over the block of the squared gradient entries */
   double sum_sq = 0.0;
   for (uint64_t i = 0; i < n; ++i) {
     double gi = amo_grad_at(g, dtype, g_first + i * stride);
@@ -127,13 +122,16 @@ void amo_step_block(double *p, double *m, double *v, const void *g, int dtype,
     /* a comparison never selects a NaN; like the sums, max and min hand it on */
     if (any_nan) stat = NAN;
   }
+  /* the block's single second moment: running average of the statistic, then its bias correction */
   *v = (1.0 - beta2) * stat + beta2 * (*v);
-
-  /* v_hat = v / (1 - beta2^t) */
   double v_hat = *v / bias2;
 
-  /* param = param - lr * m_hat / (sqrt(v_hat) + eps), m_hat = m / (1 - beta1^t) */
+  /* every element of the block: decoupled decay, first moment, bias-corrected step.  All
+   * elements divide by the same sqrt(v_hat) + eps: eps is added outside the root. */
   for (uint64_t i = 0; i < n; ++i) {
+    p[i * stride] = p[i * stride] - lr * lambda * p[i * stride];
+    double gi = amo_grad_at(g, dtype, g_first + i * stride);
+    m[i * stride] = (1.0 - beta1) * gi + beta1 * m[i * stride];
     double m_hat = m[i * stride] / bias1;
     p[i * stride] = p[i * stride] - lr * m_hat / (sqrt(v_hat) + eps);
   }

@@ -1,5 +1,5 @@
 // Host-side layout builder (see am_layout.h).  The partition itself is the paper's
-// Algorithm 3 ("Partition for Transformers", Appendix B) already reduced by the
+// listing "Partition for Transformers" (Appendix B) already reduced by the
 // caller to one block_numel per tensor; here the v scalars are numbered and each
 // tensor is routed to the kernel variant that fits its block size.
 #include "am_layout.h"
@@ -143,7 +143,8 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     if (ti.strided) {
       const int native = grad_dtype == ADAM_MINI_GRAD_BF16 ? (tuning.bf16_vec == 8 ? 8 : 4) : 4;
       var.family = AM_FAM_STRIDED;
-      // a row must be a whole number of units, and the tensor's v slice 16-byte aligned for the scale loads
+      // a row must be a whole number of units (the per-column step scales are read one float at a time,
+      // so the tensor's v slice needs no alignment of its own)
       var.vec = (ti.n_blocks % (uint64_t)native == 0) ? native : 1;
       var.lanes = 256;
       var.upt = kStridedRows;

@@ -1,6 +1,6 @@
 """Parameter partition of Adam-mini expressed as per-tensor block descriptors.
 
-The paper's Algorithm 3 ("Partition for Transformers", Appendix B) cuts each
+The paper's listing "Partition for Transformers" (Appendix B) cuts each
 named weight along its outermost dimension: embedding / output layers by token,
 query / key by attention head, value / attention projection / MLP weights by
 output neuron, and leaves every other tensor whole.  Its "Partition for
@@ -59,7 +59,7 @@ def _has(name: str, keys: Iterable[str]) -> bool:
 
 def block_numel_for(name: str, shape: Sequence[int], n_heads: int,
                     n_kv_heads: Optional[int] = None, value_whole: bool = False) -> int:
-    """block_numel of one named tensor under Algorithm 3.
+    """block_numel of one named tensor under "Partition for Transformers" (Appendix B).
 
     n_heads / n_kv_heads: number of query heads / key heads (grouped-query
     attention keeps one block per KEY head).  value_whole=True is the appendix's
@@ -94,7 +94,7 @@ def block_numel_for(name: str, shape: Sequence[int], n_heads: int,
 def partition_transformer(named_shapes: Sequence[Tuple[str, Sequence[int]]], n_heads: int,
                           n_kv_heads: Optional[int] = None, value_whole: bool = False,
                           decay_1d: bool = False) -> List[TensorSpec]:
-    """Algorithm 3 over a list of (name, shape).  1-D tensors (norm gains, biases)
+    """"Partition for Transformers" (Appendix B) over a list of (name, shape).  1-D tensors (norm gains, biases)
     get wd_scale 0 unless decay_1d (Algorithm 1 itself decays every block; exempting
     1-D gains is the usual practice and is what the benchmark configurations use)."""
     out = []

@@ -148,7 +148,7 @@ def pin_ema_and_five_param_example(lib):
 
 
 # ---------------------------------------------------------------------------
-# P4: brute force.  Algorithm 3 ("Partition for Transformers", Appendix B)
+# P4: brute force.  The listing "Partition for Transformers" (Appendix B)
 # transcribed as a dictionary name+i -> slice param[i], and Algorithm 2 run on
 # each dictionary entry with Python floats.  The oracle is driven through the
 # (numel, block_numel) description of the same partition.

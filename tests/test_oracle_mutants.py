@@ -36,6 +36,7 @@ MUTANTS = [
     ("block id counts elements", "blocks_before += numel[k] / block_numel[k];", "blocks_before += numel[k];"),
     ("block id rounds up", "return blocks_before + elem / block_numel[tensor];", "return blocks_before + (elem + block_numel[tensor] - 1) / block_numel[tensor];"),
     ("strided blocks: gradient read with stride 1", "double gi = amo_grad_at(g, dtype, g_first + i * stride);\n    sum_sq", "double gi = amo_grad_at(g, dtype, g_first + i);\n    sum_sq"),
+    ("strided blocks: first moment reads the gradient with stride 1", "double gi = amo_grad_at(g, dtype, g_first + i * stride);\n    m[i", "double gi = amo_grad_at(g, dtype, g_first + i);\n    m[i"),
     ("strided blocks: columns taken in reverse", "uint64_t first = strided ? (uint64_t)b : (uint64_t)b * block_numel;", "uint64_t first = strided ? (uint64_t)(n_blocks - 1 - b) : (uint64_t)b * block_numel;"),
     ("strided blocks: stride is block_numel", "uint64_t stride = strided ? (uint64_t)n_blocks : 1;", "uint64_t stride = strided ? block_numel : 1;"),
     ("strided blocks: flag ignored", "uint64_t stride = strided ? (uint64_t)n_blocks : 1;", "uint64_t stride = 1;"),
