@@ -29,6 +29,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--repeats", type=int, default=10,
+                    help="timed spans of --steps steps each; ms_per_step is the median span (HIP events)")
     ap.add_argument("--workload", default="llama2_7b",
                     help="tiny | gpt2_small | llama2_7b | llama3_8b | llama2_13b")
     ap.add_argument("--adamw", action="store_true", help="AdamW-equivalent mode: every block of size 1")
@@ -45,18 +47,51 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles(workload: str, kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        if line.startswith("#") or "=" not in line:
-            continue
-        kv = dict(tok.split("=", 1) for tok in line.split("\t") if "=" in tok)
-        if kv.get("kernel") == kernel and "hbm_bytes_per_launch" in kv:
-            return float(kv["hbm_bytes_per_launch"])
-    return None
+def traffic_from_profiles(workload: str, kernel: str, with_source: bool = False):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, if there is one.
+    It is a figure of that profile run (named by with_source=True: file and the tree it was taken on),
+    not something the timed run observes: counters cannot be read from inside the process."""
+    rel = os.path.join("profiles", "hbm_traffic_%s.txt" % workload)
+    path = os.path.join(ROOT, rel)
+    found, tree = None, None
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("# tree:"):
+                tree = line.split(":", 1)[1].strip()
+            if line.startswith("#") or "=" not in line:
+                continue
+            kv = dict(tok.split("=", 1) for tok in line.split("\t") if "=" in tok)
+            if kv.get("kernel") == kernel and "hbm_bytes_per_launch" in kv:
+                found = float(kv["hbm_bytes_per_launch"])
+    if with_source:
+        return found, (None if found is None else rel + ("@" + tree if tree else ""))
+    return found
+
+
+def time_spans(torch, step_fn, steps, repeats):
+    """`repeats` spans of exactly `steps` calls of step_fn each, every span bracketed by a device
+    synchronisation on both sides and timed with HIP events on the stream the steps run on (torch's
+    current stream) and, beside them, with the host clock.  Returns per-span milliseconds (events)
+    and the host-clock figures."""
+    ev_ms, host_ms = [], []
+    for _ in range(repeats):
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        start.record()
+        for _ in range(steps):
+            step_fn()
+        stop.record()
+        torch.cuda.synchronize()
+        host_ms.append((time.perf_counter() - t0) * 1e3)
+        ev_ms.append(start.elapsed_time(stop))
+    return ev_ms, host_ms
+
+
+def median(xs):
+    ys = sorted(xs)
+    n = len(ys)
+    return ys[n // 2] if n % 2 else 0.5 * (ys[n // 2 - 1] + ys[n // 2])
 
 
 def cpu_baseline(wl, run, hp, target_seconds):
@@ -148,23 +183,26 @@ def main():
         del src, dst
 
     stream = torch.cuda.current_stream().cuda_stream
-    t = 0
+    counter = {"t": 0}
+
+    def one_step():
+        counter["t"] += 1
+        run.opt.step(step=counter["t"], stream=stream, **hp)
+
     for _ in range(args.warmup):
-        t += 1
-        run.opt.step(step=t, stream=stream, **hp)
+        one_step()
     torch.cuda.synchronize()
     _progress("%d warm-up steps done" % args.warmup)
-    B.adam_mini_profile_enable(run.opt.layout, args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        t += 1
-        run.opt.step(step=t, stream=stream, **hp)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    _progress("%d timed steps done" % args.steps)
+    # per-bucket HIP events (recorded by the library on the step's stream) stay on during every timed span
+    B.adam_mini_profile_enable(run.opt.layout, min(4096, args.steps * args.repeats))
+    ev_ms, host_ms = time_spans(torch, one_step, args.steps, args.repeats)
+    _progress("%d timed spans of %d steps done" % (args.repeats, args.steps))
     buckets = B.adam_mini_profile_read(run.opt.layout)
     B.adam_mini_profile_enable(run.opt.layout, 0)
+    # the host clock around a span sees what the events see plus the launch and synchronisation latency;
+    # the larger of the two medians is reported, so the figure never undercuts either clock
+    span_ms = max(median(ev_ms), median(host_ms))
+    elapsed = span_ms * 1e-3
 
     ms_per_step = elapsed * 1e3 / args.steps
     n_params = sum(s.numel for s in wl.specs)
@@ -178,9 +216,11 @@ def main():
     dom = max(buckets, key=lambda b: b["total_ms"])
     dom_ms = dom["total_ms"] / max(1, dom["timed_launches"])
     achieved = algo_bytes(dom) / (dom_ms * 1e-3) / 1e9
+    traffic, traffic_source = traffic_from_profiles(args.workload + ("_adamw" if args.adamw else ""), dom["kernel"],
+                                                    with_source=True)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic_from_profiles(args.workload + ("_adamw" if args.adamw else ""), dom["kernel"]),
+                "traffic": traffic, "traffic_source": traffic_source,
                 "kernel": dom["kernel"], "kernel_ms": round(dom_ms, 4),
                 "algorithmic_bytes_per_launch": algo_bytes(dom)}
     whole_gbs = (n_params * per_param + (0 if args.adamw else 8 * n_blocks)) / (ms_per_step * 1e-3) / 1e9
@@ -190,6 +230,14 @@ def main():
         "unit": "Gparams/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "timing": {"clock": "HIP events on the step's stream, host clock beside them; per span: synchronize, "
+                            "%d steps, synchronize" % args.steps,
+                   "repeats": args.repeats, "span_ms_median": round(span_ms, 3),
+                   "ms_per_step_min": round(min(ev_ms) / args.steps, 4),
+                   "ms_per_step_median_events": round(median(ev_ms) / args.steps, 4),
+                   "ms_per_step_median_host": round(median(host_ms) / args.steps, 4),
+                   "ms_per_step_max": round(max(max(ev_ms), max(host_ms)) / args.steps, 4),
+                   "span_at_least_100ms": bool(span_ms >= 100.0)},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name + ("_adamw" if args.adamw else "") + ("" if args.reducer == "mean" else "_" + args.reducer),
@@ -217,8 +265,8 @@ def main():
 
 
 def other_configs(primary, torch, B, workloads, DeviceState):
-    """Throughput and HBM fraction of every BASELINE configuration on this GPU: the timed workload above plus a
-    short run (2 warm-up + 5 timed steps) of each of the others that fits the device, same launch configuration."""
+    """Throughput and HBM fraction of every BASELINE configuration on this GPU: the timed workload above plus, for
+    each of the others that fits the device, the median of 10 spans of at least 100 ms each, same launch configuration."""
     rows = [{"workload": primary["config"]["workload"], "ms_per_step": primary["ms_per_step"],
              "Gparams_per_s": primary["value"], "algorithmic_GBps": primary["whole_step"]["algorithmic_GBps"],
              "frac_of_peak": primary["whole_step"]["frac_of_peak"]}]
@@ -238,20 +286,23 @@ def other_configs(primary, torch, B, workloads, DeviceState):
             workloads.fill_grad(run.g[k], s, wl, k, 1, row_chunk=8192)
         hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
         stream = torch.cuda.current_stream().cuda_stream
-        t, steps = 0, (200 if name == "tiny" else 5)
-        for _ in range(2):
-            t += 1
-            run.opt.step(step=t, stream=stream, **hp)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            t += 1
-            run.opt.step(step=t, stream=stream, **hp)
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
+        counter = {"t": 0}
+
+        def one_step():
+            counter["t"] += 1
+            run.opt.step(step=counter["t"], stream=stream, **hp)
+
+        for _ in range(3):
+            one_step()
+        est, _ = time_spans(torch, one_step, 3, 1)                      # sizes the spans: at least 100 ms each
+        steps = max(3, int(100.0 / max(est[0] / 3, 1e-4)) + 1)
+        ev_ms, host_ms = time_spans(torch, one_step, steps, 10)
+        ms = max(median(ev_ms), median(host_ms)) / steps
         gbs = (n_params * (16 + gb) + 8 * run.opt.num_blocks) / (ms * 1e-3) / 1e9
-        rows.append({"workload": name, "ms_per_step": round(ms, 4), "Gparams_per_s": round(n_params / ms / 1e6, 2),
-                     "algorithmic_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)})
+        rows.append({"workload": name, "ms_per_step": round(ms, 5), "Gparams_per_s": round(n_params / ms / 1e6, 2),
+                     "algorithmic_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                     "spans": 10, "steps_per_span": steps,
+                     "ms_per_step_min": round(min(ev_ms) / steps, 5), "ms_per_step_max": round(max(host_ms) / steps, 5)})
         run.close()
         del run
     torch.cuda.empty_cache()

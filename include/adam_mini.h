@@ -172,15 +172,19 @@ int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor,
  *   hp       host pointer, read during the call
  *   hip_stream  hipStream_t as void* (null = default stream); all work is enqueued there
  * m and v must be zero before the first step (t = 1).  Every device pointer must be
- * 16-byte aligned.  Tensors must not overlap each other.  The call is asynchronous
- * and never allocates or synchronises, except that the first call on a layout, and
- * any call whose three pointer lists differ from the previous call's, creates or
- * re-uploads the device work tables and waits for that upload.  Results are
- * bitwise reproducible: no atomics on floating-point data, fixed summation order.
- * A call that neither creates nor re-uploads tables enqueues kernels only (no memset, no
- * copy), so it may be captured into a HIP graph; the captured step replays with the
- * hyper-parameters and pointers it was captured with.
- * Concurrent calls on the same layout race on its scratch; use one layout per
+ * 16-byte aligned.  Tensors must not overlap each other.  The call is asynchronous:
+ * it never waits for the device, and after the first call on a layout (which creates
+ * the device work tables and scratch and uploads the tables with a blocking copy) it
+ * never allocates or copies.  When the three pointer lists differ from the previous
+ * call's, the new pointers travel to the device tables as arguments of a few small
+ * kernels enqueued on hip_stream ahead of the step's own: a caller whose gradient
+ * buffers move every step pays a few microseconds of device time, no host stall.
+ * Results are bitwise reproducible: no atomics on floating-point data, fixed
+ * summation order.  Every call enqueues kernels only (no memset, no copy) once the
+ * device state exists, so it may be captured into a HIP graph; the captured step
+ * replays with the hyper-parameters and pointers it was captured with.
+ * Calls on one layout must be ordered (one stream, or streams the caller orders):
+ * concurrent calls race on the layout's tables and scratch; use one layout per
  * stream.  Non-finite gradients are not skipped: they propagate into the block's
  * v and parameters (and no other block's).
  */
@@ -248,7 +252,10 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *   "row_blocked"        1: each wavefront of a row team owns a contiguous span of the block
  *   "stream_wg_per_cu"   the same cap for the AdamW-equivalent and large-block update kernels
  *   "strided_wg_per_cu"  the same cap for the column-block (ADAM_MINI_FLAG_STRIDED) update kernel
- *   "xcd_chunk"          row kernels: a power of two C > 0 makes each of the 8 XCDs (dies with an L2 of
+ *   "strided_rows"       column-block kernels: rows of the stored matrix per work item (multiple of 4, >= 4)
+ *   "xcd_count"          number of XCDs workgroups are dealt to round-robin (power of two; 8 on an
+ *                        unpartitioned device, the default)
+ *   "xcd_chunk"          row kernels: a power of two C > 0 makes each of the XCDs (dies with an L2 of
  *                        their own, fed workgroups round-robin) walk runs of C consecutive workgroup
  *                        passes instead of every 8th one; 0 keeps the hardware order
  *   "xcd_chunk_stream"   the same for the AdamW-equivalent and large-block kernels

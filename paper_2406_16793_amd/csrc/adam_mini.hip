@@ -51,18 +51,40 @@ struct DeviceGuard {
 
 }  // namespace
 
+// Device memory a step works in besides the caller's tensors.
+struct AmDeviceMem {
+  AmSeg* segs = nullptr;       // all buckets' segments, concatenated
+  uint32_t* keys = nullptr;    // [2 * n_segs]: item_first of every segment, then lblock_first
+  float* partials = nullptr;   // LARGE: one float per chunk; STRIDED: [row chunks][columns] per tensor
+  float* scales = nullptr;     // LARGE: one step scale per large block; STRIDED: one per column
+};
+
+// The pointer lists a segment table currently holds.
+struct AmPointerCache {
+  bool valid = false;
+  std::vector<const void*> p, g, m;
+  bool same(void* const* params, const void* const* grads, void* const* exp_avg, size_t n) const {
+    return valid && std::memcmp(p.data(), params, n * sizeof(void*)) == 0 &&
+           std::memcmp(g.data(), grads, n * sizeof(void*)) == 0 &&
+           std::memcmp(m.data(), exp_avg, n * sizeof(void*)) == 0;
+  }
+  void keep(void* const* params, const void* const* grads, void* const* exp_avg, size_t n) {
+    std::memcpy(p.data(), params, n * sizeof(void*));
+    std::memcpy(g.data(), grads, n * sizeof(void*));
+    std::memcpy(m.data(), exp_avg, n * sizeof(void*));
+    valid = true;
+  }
+};
+
 struct adam_mini_layout {
   AmHostLayout host;
   int device = -1;
+  size_t lds_per_cu = 160 * 1024;  // read from the device by the first call that launches
+  bool lds_per_cu_known = false;
   // device state, created by the first call that needs it
   bool device_ready = false;
-  AmSeg* segs_dev = nullptr;       // all buckets' segments, concatenated
-  AmSeg* segs_staging = nullptr;   // pinned host copy
-  uint32_t* keys_dev = nullptr;    // [2 * n_segs]: item_first of every segment, then lblock_first
-  float* partials_dev = nullptr;   // LARGE: one float per chunk; STRIDED: [row chunks][columns] per tensor
-  float* scales_dev = nullptr;     // LARGE: one step scale per large block; STRIDED: one per column
-  bool tables_valid = false;       // segs_dev holds the pointers below
-  std::vector<const void*> cached_p, cached_g, cached_m;
+  AmDeviceMem mem;                 // the layout's own allocations
+  AmPointerCache cache;            // pointer lists held by mem.segs
   // optional per-bucket timing: events[(step * n_buckets + bucket) * 2 + {0,1}]
   std::vector<hipEvent_t> events;
   uint32_t profile_capacity = 0;   // steps the pool can hold
@@ -94,16 +116,16 @@ constexpr bool am_row_ok(int vec, int lanes, int upt) {
 // Dynamic LDS bytes that leave room for exactly `cap` workgroups per CU (0 = no cap).  The kernels
 // never touch this allocation: it only bounds how many workgroups, and so how many bytes in flight,
 // a compute unit holds at once.
-constexpr size_t kLdsPerCu = 160 * 1024;
-size_t lds_for_cap(int64_t cap) {
+constexpr size_t kLdsPerCuMax = 160 * 1024;  // gfx950; the running device's figure is read at first use
+size_t lds_for_cap(int64_t cap, size_t lds_per_cu) {
   if (cap <= 0) return 0;
   if (cap > 32) cap = 32;
-  return kLdsPerCu / (size_t)cap - 1024;  // 1 KiB slack for the kernel's own static LDS
+  return lds_per_cu / (size_t)cap - kCapSlackBytes;  // the slack is for the kernel's own static LDS
 }
 
 // Kernels launched with more than 64 KB of dynamic LDS need the attribute raised once per device.
 template <typename K>
-int allow_big_lds(K kernel) {
+int allow_big_lds(K kernel, size_t lds_per_cu) {
   struct Done { const void* kernel; int device; };
   static thread_local Done done[512];
   static thread_local int n_done = 0;
@@ -112,10 +134,18 @@ int allow_big_lds(K kernel) {
   AM_HIP(hipGetDevice(&device));
   for (int i = 0; i < n_done; ++i)
     if (done[i].kernel == key && done[i].device == device) return ADAM_MINI_OK;
-  AM_HIP(hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsPerCu - 1024)));
+  AM_HIP(hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(lds_per_cu - kCapSlackBytes)));
   if (n_done < 512) done[n_done++] = Done{key, device};
   return ADAM_MINI_OK;
 }
+
+// What every launch of one call shares.
+struct AmCtx {
+  const AmTuning& t;
+  hipStream_t stream;
+  size_t lds_per_cu;
+  AmDeviceMem mem;
+};
 
 uint32_t grid_for(uint64_t groups, const AmTuning& t) {
   uint64_t g = groups;
@@ -124,17 +154,17 @@ uint32_t grid_for(uint64_t groups, const AmTuning& t) {
   return (uint32_t)g;
 }
 
-#define AM_TAB tab.segs, tab.item_keys, tab.lblock_keys, tab.n_segs, tab.xcd_shift
+#define AM_TAB tab.segs, tab.item_keys, tab.lblock_keys, tab.n_segs, tab.xcd_code
 
 // Launch one kernel with an optional occupancy cap (see lds_for_cap).
 template <typename K, typename... Args>
-int launch_capped(K kernel, uint32_t grid, uint32_t block, int64_t cap, hipStream_t stream, Args... args) {
-  const size_t lds = lds_for_cap(cap);
+int launch_capped(K kernel, uint32_t grid, uint32_t block, int64_t cap, const AmCtx& cx, Args... args) {
+  const size_t lds = lds_for_cap(cap, cx.lds_per_cu);
   if (lds > 0) {
-    const int rc = allow_big_lds(kernel);
+    const int rc = allow_big_lds(kernel, cx.lds_per_cu);
     if (rc != ADAM_MINI_OK) return rc;
   }
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), lds, stream, args...);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), lds, cx.stream, args...);
   return ADAM_MINI_OK;
 }
 
@@ -153,17 +183,16 @@ int64_t row_cap(const AmBucket& bk, int teams, size_t grad_bytes, const AmTuning
 }
 
 template <typename G, int VEC>
-int launch_row(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc,
-               const AmTuning& t, hipStream_t stream) {
+int launch_row(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+  const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
 #define X(L, U)                                                                                       \
   if constexpr (am_row_ok(VEC, L, U)) {                                                               \
     if (var.lanes == L && var.upt == U) {                                                             \
       constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                               \
-      const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                            \
-      return launch_capped(am_row_kernel<G, VEC, L, U>, grid, WG, row_cap(bk, TEAMS, sizeof(G), t),   \
-                           stream, AM_TAB,                                                            \
-                           n_items, (uint32_t)(t.row_blocked != 0), v, sc);                           \
+      const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, cx.t);                         \
+      return launch_capped(am_row_kernel<G, VEC, L, U>, grid, WG, row_cap(bk, TEAMS, sizeof(G), cx.t), cx, \
+                           AM_TAB, n_items, (uint32_t)(cx.t.row_blocked != 0), v, sc);                \
     }                                                                                                 \
   }
   AM_ROW_VARIANTS(X)
@@ -172,15 +201,15 @@ int launch_row(const AmVariant& var, const AmBucket& bk, const AmTable& tab, flo
 }
 
 template <int VEC>
-int launch_row_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids,
-                   const AmTuning& t, hipStream_t stream) {
+int launch_row_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmCtx& cx) {
+  const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
 #define X(L, U)                                                                                       \
   if (var.lanes == L && var.upt == U) {                                                               \
     constexpr int WG = AmRowGeom<L>::WG, TEAMS = AmRowGeom<L>::TEAMS;                                 \
-    const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, t);                              \
-    hipLaunchKernelGGL((am_row_ids<VEC, L, U>), dim3(grid), dim3(WG), 0, stream, AM_TAB, n_items,        \
-                       (uint32_t)(t.row_blocked != 0), tensor, ids);                                  \
+    const uint32_t grid = grid_for((bk.n_items + TEAMS - 1) / TEAMS, cx.t);                           \
+    hipLaunchKernelGGL((am_row_ids<VEC, L, U>), dim3(grid), dim3(WG), 0, cx.stream, AM_TAB, n_items,  \
+                       (uint32_t)(cx.t.row_blocked != 0), tensor, ids);                               \
     return ADAM_MINI_OK;                                                                              \
   }
   AM_ROW_VARIANTS(X)
@@ -189,80 +218,102 @@ int launch_row_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab,
 }
 
 template <typename G, int VEC>
-int launch_row_lds(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmTuning& t,
-                   hipStream_t stream) {
+int launch_row_lds(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
   if constexpr (VEC == 1) {
     return ADAM_MINI_INVALID_ARG;  // the layout builder never stages scalar-unit blocks
   } else {
     const uint32_t n_items = (uint32_t)bk.n_items;
-    const uint32_t grid = grid_for(bk.n_items, t);
+    const uint32_t grid = grid_for(bk.n_items, cx.t);
     const size_t lds = (size_t)((bk.lds_bytes + 15) & ~15ull);
-    if (lds > kLdsPerCu - 1024) return ADAM_MINI_INVALID_ARG;
-    const int rc = allow_big_lds(am_row_lds_kernel<G, VEC>);
+    if (lds > cx.lds_per_cu - kCapSlackBytes) return ADAM_MINI_INVALID_ARG;
+    const int rc = allow_big_lds(am_row_lds_kernel<G, VEC>, cx.lds_per_cu);
     if (rc != ADAM_MINI_OK) return rc;
-    hipLaunchKernelGGL((am_row_lds_kernel<G, VEC>), dim3(grid), dim3(kLdsRowThreads), lds, stream, AM_TAB, n_items,
-                       v, sc);
+    hipLaunchKernelGGL((am_row_lds_kernel<G, VEC>), dim3(grid), dim3(kLdsRowThreads), lds, cx.stream, AM_TAB,
+                       n_items, v, sc);
     return ADAM_MINI_OK;
   }
 }
 
 template <int VEC>
-int launch_row_lds_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmTuning& t,
-                       hipStream_t stream) {
+int launch_row_lds_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmCtx& cx) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t grid = grid_for(bk.n_items, t);
-  hipLaunchKernelGGL((am_row_lds_ids<VEC>), dim3(grid), dim3(kLdsRowThreads), 0, stream, AM_TAB, n_items, tensor,
+  const uint32_t grid = grid_for(bk.n_items, cx.t);
+  hipLaunchKernelGGL((am_row_lds_ids<VEC>), dim3(grid), dim3(kLdsRowThreads), 0, cx.stream, AM_TAB, n_items, tensor,
                      ids);
   return ADAM_MINI_OK;
 }
 
+// Two units of a row per lane exist for bf16 gradients in 4-element units only.
+template <typename G, int VEC, int CPL>
+constexpr bool am_strided_ok() {
+  return CPL == 1 || (sizeof(G) == 2 && VEC == 4);
+}
+
+template <typename G, int VEC, int CPL>
+int launch_strided_cpl(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+  if constexpr (!am_strided_ok<G, VEC, CPL>()) {
+    return ADAM_MINI_INVALID_ARG;
+  } else {
+    const uint32_t n_items = (uint32_t)bk.n_items;
+    const uint32_t n_cols = (uint32_t)bk.n_lblocks;
+    const uint32_t rows = (uint32_t)bk.var.upt;
+    const uint32_t grid = grid_for(bk.n_items, cx.t);
+    const uint32_t fgrid = grid_for((bk.n_lblocks + 255) / 256, cx.t);
+    hipLaunchKernelGGL((am_strided_partial<G, VEC, CPL>), dim3(grid), dim3(kStridedThreads), 0, cx.stream, AM_TAB,
+                       n_items, rows, cx.mem.partials);
+    hipLaunchKernelGGL(am_strided_finalize, dim3(fgrid), dim3(256), 0, cx.stream, AM_TAB, n_cols, rows,
+                       (const float*)cx.mem.partials, v, cx.mem.scales, sc);
+    return launch_capped(am_strided_update<G, VEC, CPL>, grid, kStridedThreads, cx.t.strided_wg_per_cu, cx, AM_TAB,
+                         n_items, rows, (const float*)cx.mem.scales, sc);
+  }
+}
+
 template <typename G, int VEC>
-int launch_strided(const AmBucket& bk, const AmTable& tab, float* v, float* partials, float* scales,
-                   const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
-  const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_cols = (uint32_t)bk.n_lblocks;
-  const uint32_t grid = grid_for(bk.n_items, t);
-  const uint32_t fgrid = grid_for((bk.n_lblocks + 255) / 256, t);
-  hipLaunchKernelGGL((am_strided_partial<G, VEC>), dim3(grid), dim3(kStridedThreads), 0, stream, AM_TAB, n_items,
-                     partials);
-  hipLaunchKernelGGL(am_strided_finalize, dim3(fgrid), dim3(256), 0, stream, AM_TAB, n_cols,
-                     (const float*)partials, v, scales, sc);
-  return launch_capped(am_strided_update<G, VEC>, grid, kStridedThreads, t.strided_wg_per_cu, stream, AM_TAB,
-                       n_items, (const float*)scales, sc);
+int launch_strided(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+  if (bk.var.upt <= 0) return ADAM_MINI_INVALID_ARG;
+  if (bk.var.aux == 2) return launch_strided_cpl<G, VEC, 2>(bk, tab, v, sc, cx);
+  return launch_strided_cpl<G, VEC, 1>(bk, tab, v, sc, cx);
 }
 
 template <int VEC>
-int launch_strided_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmTuning& t,
-                       hipStream_t stream) {
+int launch_strided_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmCtx& cx) {
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t grid = grid_for(bk.n_items, t);
-  hipLaunchKernelGGL((am_strided_ids<VEC>), dim3(grid), dim3(kStridedThreads), 0, stream, AM_TAB, n_items, tensor,
-                     ids);
+  const uint32_t rows = (uint32_t)bk.var.upt;
+  const uint32_t grid = grid_for(bk.n_items, cx.t);
+  if (bk.var.upt <= 0) return ADAM_MINI_INVALID_ARG;
+  if (bk.var.aux == 2)
+    hipLaunchKernelGGL((am_strided_ids<VEC, 2>), dim3(grid), dim3(kStridedThreads), 0, cx.stream, AM_TAB, n_items,
+                       rows, tensor, ids);
+  else
+    hipLaunchKernelGGL((am_strided_ids<VEC, 1>), dim3(grid), dim3(kStridedThreads), 0, cx.stream, AM_TAB, n_items,
+                       rows, tensor, ids);
   return ADAM_MINI_OK;
 }
 
 template <typename G, int VEC>
-int launch_large(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v, float* partials,
-                 float* scales, const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
+int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+  const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
   const uint32_t n_lblocks = (uint32_t)bk.n_lblocks;
-  const uint32_t grid = grid_for(bk.n_items, t);
-  const uint32_t fgrid = grid_for((bk.n_lblocks + 3) / 4, t);
-  const uint32_t pgrid = grid_for((bk.n_items + 3) / 4, t);
-#define X(L, U)                                                                                        \
-  if constexpr (VEC * U <= 64) { /* larger chunks are never chosen: they would not fit the registers */ \
-    if (var.lanes == L && var.upt == U) {                                                              \
-      if (bk.alt_reducer)                                                                              \
-        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, true>), dim3(pgrid), dim3(256), 0, stream,  \
-                           AM_TAB, n_items, partials);                                                 \
-      else                                                                                             \
-        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, false>), dim3(pgrid), dim3(256), 0, stream, \
-                           AM_TAB, n_items, partials);                                                 \
-      hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, stream, AM_TAB, n_lblocks,         \
-                         (const float*)partials, v, scales, sc);                                       \
-      return launch_capped(am_large_update<G, VEC, L, U>, grid, L, t.stream_wg_per_cu, stream, AM_TAB, \
-                           n_items, (const float*)scales, sc);                                         \
-    }                                                                                                  \
+  const uint32_t grid = grid_for(bk.n_items, cx.t);
+  const uint32_t fgrid = grid_for((bk.n_lblocks + 3) / 4, cx.t);
+  const uint32_t pgrid = grid_for((bk.n_items + 3) / 4, cx.t);
+  float* partials = cx.mem.partials;
+  float* scales = cx.mem.scales;
+#define X(L, U)                                                                                          \
+  if constexpr (VEC * U <= 64) { /* larger chunks are never chosen: they would not fit the registers */  \
+    if (var.lanes == L && var.upt == U) {                                                                \
+      if (bk.alt_reducer)                                                                                \
+        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, true>), dim3(pgrid), dim3(256), 0, cx.stream, \
+                           AM_TAB, n_items, partials);                                                   \
+      else                                                                                               \
+        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, false>), dim3(pgrid), dim3(256), 0,           \
+                           cx.stream, AM_TAB, n_items, partials);                                        \
+      hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, cx.stream, AM_TAB, n_lblocks,     \
+                         (const float*)partials, v, scales, sc);                                         \
+      return launch_capped(am_large_update<G, VEC, L, U>, grid, L, cx.t.stream_wg_per_cu, cx, AM_TAB,    \
+                           n_items, (const float*)scales, sc);                                           \
+    }                                                                                                    \
   }
   AM_LARGE_VARIANTS(X)
 #undef X
@@ -270,13 +321,13 @@ int launch_large(const AmVariant& var, const AmBucket& bk, const AmTable& tab, f
 }
 
 template <int VEC>
-int launch_large_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids,
-                     const AmTuning& t, hipStream_t stream) {
+int launch_large_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmCtx& cx) {
+  const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t grid = grid_for(bk.n_items, t);
+  const uint32_t grid = grid_for(bk.n_items, cx.t);
 #define X(L, U)                                                                                      \
   if (var.lanes == L && var.upt == U) {                                                              \
-    hipLaunchKernelGGL((am_large_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, AM_TAB, n_items,      \
+    hipLaunchKernelGGL((am_large_ids<VEC, L, U>), dim3(grid), dim3(L), 0, cx.stream, AM_TAB, n_items, \
                        tensor, ids);                                                                 \
     return ADAM_MINI_OK;                                                                             \
   }
@@ -286,13 +337,13 @@ int launch_large_ids(const AmVariant& var, const AmBucket& bk, const AmTable& ta
 }
 
 template <typename G, int VEC>
-int launch_elementwise(const AmVariant& var, const AmBucket& bk, const AmTable& tab, float* v,
-                       const AmScalars& sc, const AmTuning& t, hipStream_t stream) {
+int launch_elementwise(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+  const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t grid = grid_for(bk.n_items, t);
+  const uint32_t grid = grid_for(bk.n_items, cx.t);
 #define X(L, U)                                                                                       \
   if (var.lanes == L && var.upt == U)                                                                 \
-    return launch_capped(am_elementwise<G, VEC, L, U>, grid, L, t.stream_wg_per_cu, stream, AM_TAB,   \
+    return launch_capped(am_elementwise<G, VEC, L, U>, grid, L, cx.t.stream_wg_per_cu, cx, AM_TAB,    \
                          n_items, v, sc);
   AM_EW_VARIANTS(X)
 #undef X
@@ -300,14 +351,15 @@ int launch_elementwise(const AmVariant& var, const AmBucket& bk, const AmTable& 
 }
 
 template <int VEC>
-int launch_elementwise_ids(const AmVariant& var, const AmBucket& bk, const AmTable& tab, uint32_t tensor,
-                           uint64_t* ids, const AmTuning& t, hipStream_t stream) {
+int launch_elementwise_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids,
+                           const AmCtx& cx) {
+  const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t grid = grid_for(bk.n_items, t);
+  const uint32_t grid = grid_for(bk.n_items, cx.t);
 #define X(L, U)                                                                                          \
   if (var.lanes == L && var.upt == U) {                                                                  \
-    hipLaunchKernelGGL((am_elementwise_ids<VEC, L, U>), dim3(grid), dim3(L), 0, stream, AM_TAB, n_items,    \
-                       tensor, ids);                                                                     \
+    hipLaunchKernelGGL((am_elementwise_ids<VEC, L, U>), dim3(grid), dim3(L), 0, cx.stream, AM_TAB,       \
+                       n_items, tensor, ids);                                                            \
     return ADAM_MINI_OK;                                                                                 \
   }
   AM_EW_VARIANTS(X)
@@ -343,43 +395,44 @@ int dispatch_vec(int vec, F f) {
   return ADAM_MINI_INVALID_ARG;
 }
 
-AmTable bucket_table(const adam_mini_layout* L, const AmBucket& bk) {
+uint32_t floor_log2(int64_t x) {
+  uint32_t r = 0;
+  while ((int64_t(1) << (r + 1)) <= x) ++r;
+  return r;
+}
+
+AmTable bucket_table(const adam_mini_layout* L, const AmDeviceMem& mem, const AmBucket& bk) {
   AmTable tab;
-  tab.segs = L->segs_dev + bk.table_offset;
-  tab.item_keys = L->keys_dev + bk.table_offset;
-  tab.lblock_keys = L->keys_dev + L->host.n_segs + bk.table_offset;
+  tab.segs = mem.segs + bk.table_offset;
+  tab.item_keys = mem.keys + bk.table_offset;
+  tab.lblock_keys = mem.keys + L->host.n_segs + bk.table_offset;
   tab.n_segs = (uint32_t)bk.segs.size();
   const AmTuning& t = L->host.tuning;
   const int fam = bk.var.family;
   const int64_t chunk = (fam == AM_FAM_ROW || fam == AM_FAM_ROW_LDS) ? t.xcd_chunk
                         : fam == AM_FAM_STRIDED                      ? t.xcd_chunk_strided
                                                                      : t.xcd_chunk_stream;
-  tab.xcd_shift = 32;  // identity
-  if (chunk > 0) {
-    tab.xcd_shift = 0;
-    while ((int64_t(1) << (tab.xcd_shift + 1)) <= chunk) ++tab.xcd_shift;
-  }
+  tab.xcd_code = 32;  // identity
+  if (chunk > 0 && t.xcd_count > 1) tab.xcd_code = floor_log2(chunk) | (floor_log2(t.xcd_count) << 8);
   return tab;
 }
 
 int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, const AmScalars& sc,
-                       hipStream_t stream) {
-  const AmTable tab = bucket_table(L, bk);
-  const AmVariant& var = bk.var;
-  const AmTuning& t = L->host.tuning;
-  return dispatch_grad(L->host.grad_dtype, var.vec, [&](auto tag) {
+                       const AmCtx& cx) {
+  const AmTable tab = bucket_table(L, cx.mem, bk);
+  return dispatch_grad(L->host.grad_dtype, bk.var.vec, [&](auto tag) {
     using T = decltype(tag);
-    switch (var.family) {
+    switch (bk.var.family) {
       case AM_FAM_ROW:
-        return launch_row<typename T::G, T::VEC>(var, bk, tab, v, sc, t, stream);
+        return launch_row<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       case AM_FAM_ROW_LDS:
-        return launch_row_lds<typename T::G, T::VEC>(bk, tab, v, sc, t, stream);
+        return launch_row_lds<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       case AM_FAM_STRIDED:
-        return launch_strided<typename T::G, T::VEC>(bk, tab, v, L->partials_dev, L->scales_dev, sc, t, stream);
+        return launch_strided<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       case AM_FAM_LARGE:
-        return launch_large<typename T::G, T::VEC>(var, bk, tab, v, L->partials_dev, L->scales_dev, sc, t, stream);
+        return launch_large<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       case AM_FAM_ELEMENTWISE:
-        return launch_elementwise<typename T::G, T::VEC>(var, bk, tab, v, sc, t, stream);
+        return launch_elementwise<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       default:
         return (int)ADAM_MINI_INVALID_ARG;
     }
@@ -387,23 +440,21 @@ int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, 
 }
 
 int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t tensor, uint64_t* ids,
-                      hipStream_t stream) {
-  const AmTable tab = bucket_table(L, bk);
-  const AmVariant& var = bk.var;
-  const AmTuning& t = L->host.tuning;
-  return dispatch_vec(var.vec, [&](auto tag) {
+                      const AmCtx& cx) {
+  const AmTable tab = bucket_table(L, cx.mem, bk);
+  return dispatch_vec(bk.var.vec, [&](auto tag) {
     constexpr int VEC = decltype(tag)::VEC;
-    switch (var.family) {
+    switch (bk.var.family) {
       case AM_FAM_ROW:
-        return launch_row_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
+        return launch_row_ids<VEC>(bk, tab, tensor, ids, cx);
       case AM_FAM_ROW_LDS:
-        return launch_row_lds_ids<VEC>(bk, tab, tensor, ids, t, stream);
+        return launch_row_lds_ids<VEC>(bk, tab, tensor, ids, cx);
       case AM_FAM_STRIDED:
-        return launch_strided_ids<VEC>(bk, tab, tensor, ids, t, stream);
+        return launch_strided_ids<VEC>(bk, tab, tensor, ids, cx);
       case AM_FAM_LARGE:
-        return launch_large_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
+        return launch_large_ids<VEC>(bk, tab, tensor, ids, cx);
       case AM_FAM_ELEMENTWISE:
-        return launch_elementwise_ids<VEC>(var, bk, tab, tensor, ids, t, stream);
+        return launch_elementwise_ids<VEC>(bk, tab, tensor, ids, cx);
       default:
         return (int)ADAM_MINI_INVALID_ARG;
     }
@@ -413,39 +464,81 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
 // ---------------------------------------------------------------------------
 // device tables
 // ---------------------------------------------------------------------------
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Byte layout of the work tables inside one allocation.
+struct AmTableBytes {
+  size_t segs = 0, keys = 0, partials = 0, scales = 0, total = 0;  // offsets, then the size
+};
+
+AmTableBytes table_bytes(const AmHostLayout& h) {
+  AmTableBytes b;
+  b.segs = 0;
+  b.keys = round_up(h.n_segs * sizeof(AmSeg), 256);
+  b.partials = b.keys + round_up(2 * h.n_segs * sizeof(uint32_t), 256);
+  b.scales = b.partials + round_up(h.n_partials * sizeof(float), 256);
+  b.total = b.scales + round_up(h.n_lblocks * sizeof(float), 256);
+  return b;
+}
+
+AmDeviceMem carve(unsigned char* base, const AmTableBytes& b) {
+  AmDeviceMem m;
+  m.segs = reinterpret_cast<AmSeg*>(base + b.segs);
+  m.keys = reinterpret_cast<uint32_t*>(base + b.keys);
+  m.partials = reinterpret_cast<float*>(base + b.partials);
+  m.scales = reinterpret_cast<float*>(base + b.scales);
+  return m;
+}
+
+// Host image of the segment and key tables ([0, b.partials) of the byte layout) with the given pointer
+// lists (null lists: pointers stay null, which is enough for the id kernels).
+std::vector<unsigned char> table_image(const adam_mini_layout* L, const AmTableBytes& b, void* const* params,
+                                       const void* const* grads, void* const* exp_avg) {
+  std::vector<unsigned char> img(b.partials, 0);
+  AmSeg* segs = reinterpret_cast<AmSeg*>(img.data() + b.segs);
+  uint32_t* keys = reinterpret_cast<uint32_t*>(img.data() + b.keys);
+  const size_t n = L->host.n_segs;
+  for (const AmBucket& bk : L->host.buckets)
+    for (size_t i = 0; i < bk.segs.size(); ++i) {
+      AmSeg s = bk.segs[i];
+      if (params) {
+        s.p = (float*)params[s.tensor];
+        s.g = grads[s.tensor];
+        s.m = (float*)exp_avg[s.tensor];
+      }
+      segs[bk.table_offset + i] = s;
+      keys[bk.table_offset + i] = s.item_first;
+      keys[n + bk.table_offset + i] = s.lblock_first;
+    }
+  return img;
+}
+
 void free_device_state(adam_mini_layout* L) {
-  if (L->segs_dev) (void)hipFree(L->segs_dev);
-  if (L->segs_staging) (void)hipHostFree(L->segs_staging);
-  if (L->keys_dev) (void)hipFree(L->keys_dev);
-  if (L->partials_dev) (void)hipFree(L->partials_dev);
-  if (L->scales_dev) (void)hipFree(L->scales_dev);
-  L->segs_dev = nullptr;
-  L->segs_staging = nullptr;
-  L->keys_dev = nullptr;
-  L->partials_dev = nullptr;
-  L->scales_dev = nullptr;
+  if (L->mem.segs) (void)hipFree(L->mem.segs);  // one allocation: the other pointers lie inside it
+  L->mem = AmDeviceMem();
   L->device_ready = false;
-  L->tables_valid = false;
+  L->cache.valid = false;
+}
+
+// LDS of a compute unit, from the device (gfx950: 160 KB).
+int query_device(adam_mini_layout* L) {
+  int lds = 0;
+  AM_HIP(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, L->device));
+  if (lds >= 64 * 1024 && (size_t)lds <= kLdsPerCuMax) L->lds_per_cu = (size_t)lds;
+  return ADAM_MINI_OK;
 }
 
 int allocate_device_state(adam_mini_layout* L) {
-  const size_t n = L->host.n_segs;
-  AM_HIP(hipMalloc((void**)&L->segs_dev, n * sizeof(AmSeg)));
-  AM_HIP(hipHostMalloc((void**)&L->segs_staging, n * sizeof(AmSeg), hipHostMallocDefault));
-  AM_HIP(hipMalloc((void**)&L->keys_dev, 2 * n * sizeof(uint32_t)));
-  if (L->host.n_partials > 0) {
-    AM_HIP(hipMalloc((void**)&L->partials_dev, L->host.n_partials * sizeof(float)));
-    AM_HIP(hipMalloc((void**)&L->scales_dev, L->host.n_lblocks * sizeof(float)));
-  }
-  // the key arrays never change: upload them once
-  std::vector<uint32_t> keys(2 * n, 0u);
-  for (const AmBucket& bk : L->host.buckets)
-    for (size_t i = 0; i < bk.segs.size(); ++i) {
-      keys[bk.table_offset + i] = bk.segs[i].item_first;
-      keys[n + bk.table_offset + i] = bk.segs[i].lblock_first;
-    }
-  AM_HIP(hipMemcpy(L->keys_dev, keys.data(), keys.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
-  return ADAM_MINI_OK;
+  const AmTableBytes b = table_bytes(L->host);
+  unsigned char* base = nullptr;
+  AM_HIP(hipMalloc((void**)&base, b.total));
+  L->mem = carve(base, b);
+  // the tables without data pointers; a step fills those in with am_write_pointers
+  const std::vector<unsigned char> img = table_image(L, b, nullptr, nullptr, nullptr);
+  AM_HIP(hipMemcpy(base, img.data(), img.size(), hipMemcpyHostToDevice));
+  const int rc = query_device(L);
+  if (rc == ADAM_MINI_OK) L->lds_per_cu_known = true;
+  return rc;
 }
 
 // Device tables and scratch, created by the first call that needs them.  On failure nothing is kept.
@@ -465,27 +558,82 @@ int ensure_device_state(adam_mini_layout* L) {
   return ADAM_MINI_OK;
 }
 
-// Upload the work tables with the given pointer lists (null lists: pointers stay null,
-// which is enough for the id kernels).  Waits for the upload so the staging buffer can be reused.
-int upload_tables(adam_mini_layout* L, void* const* params, const void* const* grads, void* const* exp_avg,
-                  hipStream_t stream) {
-  for (const AmBucket& bk : L->host.buckets) {
+// New pointer lists for the layout's own segment table: sent as kernel arguments, kPointersPerLaunch
+// segments per launch, in stream order before the step's kernels.  No copy, no wait.
+int write_pointers(adam_mini_layout* L, void* const* params, const void* const* grads, void* const* exp_avg,
+                   hipStream_t stream) {
+  AmPointerBatch batch;
+  uint32_t first = 0, n = 0;
+  const uint32_t total = (uint32_t)L->host.n_segs;
+  for (const AmBucket& bk : L->host.buckets)
     for (size_t i = 0; i < bk.segs.size(); ++i) {
-      AmSeg s = bk.segs[i];
-      if (params) {
-        s.p = (float*)params[s.tensor];
-        s.g = grads[s.tensor];
-        s.m = (float*)exp_avg[s.tensor];
+      const uint32_t k = bk.segs[i].tensor;
+      batch.t[n++] = AmPointerTriple{(float*)params[k], grads[k], (float*)exp_avg[k]};
+      if (n == (uint32_t)kPointersPerLaunch || first + n == total) {
+        hipLaunchKernelGGL(am_write_pointers, dim3(1), dim3(256), 0, stream, L->mem.segs, first, n, batch);
+        first += n;
+        n = 0;
       }
-      L->segs_staging[bk.table_offset + i] = s;
     }
-  }
-  AM_HIP(hipMemcpyAsync(L->segs_dev, L->segs_staging, L->host.n_segs * sizeof(AmSeg), hipMemcpyHostToDevice, stream));
-  AM_HIP(hipStreamSynchronize(stream));
+  AM_HIP(hipGetLastError());
   return ADAM_MINI_OK;
 }
 
 bool finite_f(float x) { return std::isfinite(x); }
+
+// Everything adam_mini_step checks before it touches a device.
+int validate_step(const adam_mini_layout* layout, void* const* params, const void* const* grads,
+                  void* const* exp_avg, const float* v_dev, const adam_mini_hparams* hp) {
+  if (!layout || !params || !grads || !exp_avg || !v_dev || !hp) return ADAM_MINI_INVALID_ARG;
+  if (hp->step == 0) return ADAM_MINI_INVALID_ARG;
+  if (!finite_f(hp->lr) || !finite_f(hp->weight_decay) || !finite_f(hp->eps) || hp->eps < 0.0f)
+    return ADAM_MINI_INVALID_ARG;
+  if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
+    return ADAM_MINI_INVALID_ARG;
+  const size_t n = layout->host.tensors.size();
+  for (size_t k = 0; k < n; ++k)
+    if (!params[k] || !grads[k] || !exp_avg[k]) return ADAM_MINI_INVALID_ARG;
+  if (((uintptr_t)v_dev & 15u) != 0) return ADAM_MINI_MISALIGNED;
+  for (size_t k = 0; k < n; ++k)
+    if ((((uintptr_t)params[k] | (uintptr_t)grads[k] | (uintptr_t)exp_avg[k]) & 15u) != 0) return ADAM_MINI_MISALIGNED;
+  if (layout->device < 0) return ADAM_MINI_NO_DEVICE;
+  return ADAM_MINI_OK;
+}
+
+// Step scalars in double, rounded once.
+AmScalars step_scalars(const adam_mini_hparams* hp) {
+  const double b1 = hp->beta1, b2 = hp->beta2, t = (double)hp->step;
+  const double bc1 = 1.0 - std::pow(b1, t), bc2 = 1.0 - std::pow(b2, t);
+  AmScalars sc;
+  sc.beta1 = hp->beta1;
+  sc.omb1 = (float)(1.0 - b1);
+  sc.beta2 = hp->beta2;
+  sc.omb2 = (float)(1.0 - b2);
+  sc.eps = hp->eps;
+  sc.bc2 = (float)bc2;
+  sc.step_size = (float)((double)hp->lr / bc1);
+  sc.lr_wd = (float)((double)hp->lr * (double)hp->weight_decay);
+  return sc;
+}
+
+// The launches of one step, with the tables and scratch of `mem`.
+int launch_step(adam_mini_layout* layout, const AmDeviceMem& mem, float* v_dev, const adam_mini_hparams* hp,
+                hipStream_t stream) {
+  const AmScalars sc = step_scalars(hp);
+  const AmCtx cx{layout->host.tuning, stream, layout->lds_per_cu, mem};
+  const size_t nb = layout->host.buckets.size();
+  const bool timed = layout->profile_used < layout->profile_capacity;
+  for (size_t b = 0; b < nb; ++b) {
+    hipEvent_t* ev = timed ? &layout->events[((size_t)layout->profile_used * nb + b) * 2] : nullptr;
+    if (ev) AM_HIP(hipEventRecord(ev[0], stream));
+    const int rc = launch_bucket_step(layout, layout->host.buckets[b], v_dev, sc, cx);
+    if (rc != ADAM_MINI_OK) return rc;
+    if (ev) AM_HIP(hipEventRecord(ev[1], stream));
+  }
+  if (timed) layout->profile_used++;
+  AM_HIP(hipGetLastError());
+  return ADAM_MINI_OK;
+}
 
 }  // namespace
 
@@ -507,7 +655,7 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "max_upt") g_tuning.max_upt = value;
   else if (k == "row_max_units") g_tuning.row_max_units = value;
   else if (k == "lds_max_bytes") {
-    if (value > (int64_t)(kLdsPerCu - 1024)) return ADAM_MINI_INVALID_ARG;
+    if (value > (int64_t)(kLdsPerCuMax - kCapSlackBytes)) return ADAM_MINI_INVALID_ARG;
     g_tuning.lds_max_bytes = value;
   }
   else if (k == "large_chunk_upt") g_tuning.large_chunk_upt = value;
@@ -518,6 +666,14 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "row_blocked") g_tuning.row_blocked = value;
   else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
   else if (k == "strided_wg_per_cu") g_tuning.strided_wg_per_cu = value;
+  else if (k == "strided_rows") {
+    if (value < 4 || value > 65536 || value % 4 != 0) return ADAM_MINI_INVALID_ARG;
+    g_tuning.strided_rows = value;
+  }
+  else if (k == "xcd_count") {
+    if (value < 1 || value > 64 || (value & (value - 1)) != 0) return ADAM_MINI_INVALID_ARG;
+    g_tuning.xcd_count = value;
+  }
   else if (k == "xcd_chunk" || k == "xcd_chunk_stream" || k == "xcd_chunk_strided") {
     if (value > (int64_t(1) << 20) || (value & (value - 1)) != 0) return ADAM_MINI_INVALID_ARG;
     (k == "xcd_chunk" ? g_tuning.xcd_chunk : k == "xcd_chunk_stream" ? g_tuning.xcd_chunk_stream
@@ -543,9 +699,11 @@ int adam_mini_init_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors
   try {
     rc = am_build_layout(descs, n_tensors, grad_dtype, tuning, &L->host);
     if (rc == ADAM_MINI_OK) {
-      L->cached_p.assign(n_tensors, nullptr);
-      L->cached_g.assign(n_tensors, nullptr);
-      L->cached_m.assign(n_tensors, nullptr);
+      for (AmPointerCache* c : {&L->cache}) {
+        c->p.assign(n_tensors, nullptr);
+        c->g.assign(n_tensors, nullptr);
+        c->m.assign(n_tensors, nullptr);
+      }
     }
   } catch (const std::bad_alloc&) {
     rc = ADAM_MINI_OUT_OF_MEMORY;
@@ -596,13 +754,10 @@ int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor, uint64_
   if (rc != ADAM_MINI_OK) return rc;
   rc = ensure_device_state(layout);
   if (rc != ADAM_MINI_OK) return rc;
-  if (!layout->tables_valid) {
-    // no step yet: upload the tables without data pointers (the id kernels do not use them)
-    rc = upload_tables(layout, nullptr, nullptr, nullptr, stream);
-    if (rc != ADAM_MINI_OK) return rc;
-  }
+  // the id kernels read the tables created above and no data pointer
   const AmBucket& bk = layout->host.buckets[layout->host.tensors[tensor].bucket];
-  rc = launch_bucket_ids(layout, bk, tensor, ids_dev, stream);
+  const AmCtx cx{layout->host.tuning, stream, layout->lds_per_cu, layout->mem};
+  rc = launch_bucket_ids(layout, bk, tensor, ids_dev, cx);
   if (rc != ADAM_MINI_OK) return rc;
   AM_HIP(hipGetLastError());
   return ADAM_MINI_OK;
@@ -610,65 +765,22 @@ int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor, uint64_
 
 int adam_mini_step(adam_mini_layout* layout, void* const* params, const void* const* grads, void* const* exp_avg,
                    float* v_dev, const adam_mini_hparams* hp, void* hip_stream) {
-  if (!layout || !params || !grads || !exp_avg || !v_dev || !hp) return ADAM_MINI_INVALID_ARG;
-  if (hp->step == 0) return ADAM_MINI_INVALID_ARG;
-  if (!finite_f(hp->lr) || !finite_f(hp->weight_decay) || !finite_f(hp->eps) || hp->eps < 0.0f)
-    return ADAM_MINI_INVALID_ARG;
-  if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
-    return ADAM_MINI_INVALID_ARG;
-  const size_t n = layout->host.tensors.size();
-  for (size_t k = 0; k < n; ++k)
-    if (!params[k] || !grads[k] || !exp_avg[k]) return ADAM_MINI_INVALID_ARG;
-  if (((uintptr_t)v_dev & 15u) != 0) return ADAM_MINI_MISALIGNED;
-  for (size_t k = 0; k < n; ++k)
-    if ((((uintptr_t)params[k] | (uintptr_t)grads[k] | (uintptr_t)exp_avg[k]) & 15u) != 0) return ADAM_MINI_MISALIGNED;
-  if (layout->device < 0) return ADAM_MINI_NO_DEVICE;
-
+  int rc = validate_step(layout, params, grads, exp_avg, v_dev, hp);
+  if (rc != ADAM_MINI_OK) return rc;
   hipStream_t stream = (hipStream_t)hip_stream;
   DeviceGuard guard;
-  int rc = guard.enter(layout->device);
+  rc = guard.enter(layout->device);
   if (rc != ADAM_MINI_OK) return rc;
   rc = ensure_device_state(layout);
   if (rc != ADAM_MINI_OK) return rc;
-
-  const bool same = layout->tables_valid && std::memcmp(layout->cached_p.data(), params, n * sizeof(void*)) == 0 &&
-                    std::memcmp(layout->cached_g.data(), grads, n * sizeof(void*)) == 0 &&
-                    std::memcmp(layout->cached_m.data(), exp_avg, n * sizeof(void*)) == 0;
-  if (!same) {
-    layout->tables_valid = false;
-    rc = upload_tables(layout, params, grads, exp_avg, stream);
+  const size_t n = layout->host.tensors.size();
+  if (!layout->cache.same(params, grads, exp_avg, n)) {
+    layout->cache.valid = false;
+    rc = write_pointers(layout, params, grads, exp_avg, stream);
     if (rc != ADAM_MINI_OK) return rc;
-    std::memcpy(layout->cached_p.data(), params, n * sizeof(void*));
-    std::memcpy(layout->cached_g.data(), grads, n * sizeof(void*));
-    std::memcpy(layout->cached_m.data(), exp_avg, n * sizeof(void*));
-    layout->tables_valid = true;
+    layout->cache.keep(params, grads, exp_avg, n);
   }
-
-  // step scalars in double, rounded once
-  const double b1 = hp->beta1, b2 = hp->beta2, t = (double)hp->step;
-  const double bc1 = 1.0 - std::pow(b1, t), bc2 = 1.0 - std::pow(b2, t);
-  AmScalars sc;
-  sc.beta1 = hp->beta1;
-  sc.omb1 = (float)(1.0 - b1);
-  sc.beta2 = hp->beta2;
-  sc.omb2 = (float)(1.0 - b2);
-  sc.eps = hp->eps;
-  sc.bc2 = (float)bc2;
-  sc.step_size = (float)((double)hp->lr / bc1);
-  sc.lr_wd = (float)((double)hp->lr * (double)hp->weight_decay);
-
-  const size_t nb = layout->host.buckets.size();
-  const bool timed = layout->profile_used < layout->profile_capacity;
-  for (size_t b = 0; b < nb; ++b) {
-    hipEvent_t* ev = timed ? &layout->events[((size_t)layout->profile_used * nb + b) * 2] : nullptr;
-    if (ev) AM_HIP(hipEventRecord(ev[0], stream));
-    rc = launch_bucket_step(layout, layout->host.buckets[b], v_dev, sc, stream);
-    if (rc != ADAM_MINI_OK) return rc;
-    if (ev) AM_HIP(hipEventRecord(ev[1], stream));
-  }
-  if (timed) layout->profile_used++;
-  AM_HIP(hipGetLastError());
-  return ADAM_MINI_OK;
+  return launch_step(layout, layout->mem, v_dev, hp, stream);
 }
 
 uint32_t adam_mini_num_buckets(const adam_mini_layout* layout) {
@@ -748,7 +860,7 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
                         : bk.var.family == AM_FAM_LARGE ? "am_large_update"
                         : bk.var.family == AM_FAM_ROW_LDS ? "am_row_lds_kernel" : "am_elementwise";
     if (bk.var.family == AM_FAM_STRIDED)
-      std::snprintf(o.kernel, sizeof o.kernel, "am_strided_update<%s, %d>", gname, bk.var.vec);
+      std::snprintf(o.kernel, sizeof o.kernel, "am_strided_update<%s, %d, %d>", gname, bk.var.vec, bk.var.aux);
     else if (bk.var.family == AM_FAM_ROW_LDS)
       std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d>", kname, gname, bk.var.vec);
     else

@@ -28,21 +28,52 @@
       const uint32_t* __restrict__ lblock_keys, uint32_t n_segs
 #define AM_TABLE_ARGS segs, item_keys, lblock_keys, n_segs
 // What every work-item kernel takes: the tables and the XCD swizzle of its workgroup passes.
-#define AM_KERNEL_PARAMS AM_TABLE_PARAMS, uint32_t xcd_shift
+#define AM_KERNEL_PARAMS AM_TABLE_PARAMS, uint32_t xcd_code
 
 // Workgroup pass -> group of work items.  The hardware deals consecutive workgroups round-robin to
-// the 8 XCDs, each with an L2 of its own, so with the identity map the 8 dies interleave at the
-// grain of single work items over the whole address range.  The swizzle hands each die runs of
-// 2^xcd_shift consecutive groups instead: passes b, b+8, b+16, ... (all on die b % 8) walk one run,
-// and the 8 runs of a span of 8 * 2^xcd_shift groups go to the 8 dies.  It is a bijection on
-// [0, n_groups): whole spans are permuted, the ragged tail keeps the identity.  xcd_shift >= 32
-// switches it off.  Only the order in which blocks are visited changes, never a block's arithmetic.
-__device__ __forceinline__ uint32_t am_xcd_swizzle(uint32_t b, uint32_t n_groups, uint32_t xcd_shift) {
-  if (xcd_shift >= 32) return b;
-  const uint32_t span_shift = xcd_shift + 3;
+// the XCDs (8 when the device is one partition), each with an L2 of its own, so with the identity
+// map the dies interleave at the grain of single work items over the whole address range.  The
+// swizzle hands each die runs of 2^shift consecutive groups instead: passes b, b+X, b+2X, ... (all
+// on die b % X) walk one run, and the X runs of a span of X * 2^shift groups go to the X dies.  It is
+// a bijection on [0, n_groups): whole spans are permuted, the ragged tail keeps the identity.
+// `xcd_code` = shift | log2(X) << 8; shift >= 32 switches it off.  Only the order in which blocks are
+// visited changes, never a block's arithmetic.
+__device__ __forceinline__ uint32_t am_xcd_swizzle(uint32_t b, uint32_t n_groups, uint32_t xcd_code) {
+  const uint32_t shift = xcd_code & 0xffu, dies_log2 = xcd_code >> 8;
+  if (shift >= 32) return b;
+  const uint32_t span_shift = shift + dies_log2;
   if (b >= (n_groups >> span_shift) << span_shift) return b;
-  const uint32_t die = b & 7u, j = b >> 3;
-  return ((((j >> xcd_shift) << 3) + die) << xcd_shift) + (j & ((1u << xcd_shift) - 1u));
+  const uint32_t die = b & ((1u << dies_log2) - 1u), j = b >> dies_log2;
+  return ((((j >> shift) << dies_log2) + die) << shift) + (j & ((1u << shift) - 1u));
+}
+
+// Resident-workgroup caps are set by reserving dynamic LDS that the kernels never touch: cap
+// workgroups fit a compute unit when each reserves (LDS per CU) / cap - kCapSlackBytes.  The slack
+// is what a capped kernel may declare as static LDS of its own.
+constexpr int kCapSlackBytes = 1024;
+
+// ===========================================================================
+// table writers: small host tables travel to the device as kernel ARGUMENTS, so an update of the
+// work tables is an ordinary launch on the step's stream: no staging buffer, no copy, no wait.
+// ===========================================================================
+constexpr int kPointersPerLaunch = 144;  // segments per am_write_pointers launch (24 bytes each)
+struct AmPointerTriple {
+  float* p;
+  const void* g;
+  float* m;
+};
+struct AmPointerBatch {
+  AmPointerTriple t[kPointersPerLaunch];
+};
+// Fills in the data pointers of segments [first, first + n) of the concatenated segment table.
+__global__ __launch_bounds__(256) void am_write_pointers(AmSeg* __restrict__ segs, uint32_t first, uint32_t n,
+                                                         AmPointerBatch batch) {
+  if (threadIdx.x < n) {
+    AmSeg* s = segs + first + threadIdx.x;
+    s->p = batch.t[threadIdx.x].p;
+    s->g = batch.t[threadIdx.x].g;
+    s->m = batch.t[threadIdx.x].m;
+  }
 }
 
 // ===========================================================================
@@ -106,10 +137,11 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(AM_KERNEL_
   using Geom = AmRowGeom<LANES>;
   // slot [parity][w] = sum of wavefront w; slot [parity][WAVES] = the block's old v
   __shared__ float xch[2][(Geom::WAVES > 1 ? Geom::WAVES : 1) + 1];
+  static_assert(sizeof(xch) <= kCapSlackBytes, "static LDS must fit the slack the occupancy cap leaves");
   uint32_t parity = 0;
   const uint32_t n_groups = (n_items + Geom::TEAMS - 1) / Geom::TEAMS;
   for (uint32_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x, parity ^= 1u) {
-    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_shift) * Geom::TEAMS;
+    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_code) * Geom::TEAMS;
     const AmRowItem it = am_row_decode<LANES>(AM_TABLE_ARGS, n_items, first);
     const AmSeg& S = *it.seg;
     const uint64_t units = S.units_per_block;
@@ -205,7 +237,7 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_KERNEL_PAR
   using Geom = AmRowGeom<LANES>;
   const uint32_t n_groups = (n_items + Geom::TEAMS - 1) / Geom::TEAMS;
   for (uint32_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
-    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_shift) * Geom::TEAMS;
+    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_code) * Geom::TEAMS;
     const AmRowItem it = am_row_decode<LANES>(AM_TABLE_ARGS, n_items, first);
     const AmSeg& S = *it.seg;
     if (!it.active || S.tensor != tensor) continue;
@@ -245,7 +277,7 @@ __global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_KERNEL_PA
   __shared__ float xch[2][kLdsRowThreads / 64 + 1];
   uint32_t parity = 0;
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x, parity ^= 1u) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
     const AmRowItem it = am_row_decode<kLdsRowThreads>(AM_TABLE_ARGS, n_items, item);
     const AmSeg& S = *it.seg;
     const uint64_t units = S.units_per_block;
@@ -335,7 +367,7 @@ template <int VEC>
 __global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_ids(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                  uint32_t tensor, uint64_t* __restrict__ ids) {
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
     const AmRowItem it = am_row_decode<kLdsRowThreads>(AM_TABLE_ARGS, n_items, item);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;
@@ -397,7 +429,7 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint32_t n_groups = (n_items + 3) / 4;
   for (uint32_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
-    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_shift) * 4;
+    const uint32_t first = am_xcd_swizzle(grp, n_groups, xcd_code) * 4;
     uint32_t item = first + wave;
     const bool active = item < n_items;
     if (!active) item = n_items - 1;
@@ -500,7 +532,7 @@ __global__ __launch_bounds__(THREADS) void am_large_update(AM_KERNEL_PARAMS,
                                                            uint32_t n_items, const float* __restrict__ scales,
                                                            AmScalars sc) {
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     const float scale = scales[it.lblock];
@@ -535,7 +567,7 @@ __global__ __launch_bounds__(THREADS) void am_large_ids(AM_KERNEL_PARAMS,
                                                         uint32_t n_items, uint32_t tensor,
                                                         uint64_t* __restrict__ ids) {
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;
@@ -554,88 +586,99 @@ __global__ __launch_bounds__(THREADS) void am_large_ids(AM_KERNEL_PARAMS,
 
 // ===========================================================================
 // STRIDED family: the tensor is a row-major [R, C] matrix whose blocks are its C columns
-// (a weight stored transposed).  A lane owns VEC adjacent columns, a workgroup 256*VEC of them,
-// and a work item is one chunk of kStridedRows rows of that column group: every access is still a
-// contiguous 128-bit run along a row, and column sums need no cross-lane reduction at all.
-//   am_strided_partial   per item: sum of g^2 of each owned column over the row chunk
-//   am_strided_finalize  per column: fixed-order sum over the row chunks (double), v update, step scale
-//   am_strided_update    per item: m and p update with the per-column step scales
+// (a weight stored transposed).  A work item is a tile: `rows_per_item` consecutive rows of a group
+// of 256 * CPL units (256 * CPL * VEC columns).  Every access is a contiguous 128-bit run along a
+// row, and column sums need no cross-lane reduction at all: a lane only ever adds up its own columns.
+//   am_strided_partial   per tile: the statistic of g^2 of each column over the tile's rows
+//   am_strided_finalize  per column: fixed-order combination over the row chunks (double), v update, step scale
+//   am_strided_update    per tile: m and p update with the per-column step scales
+// CPL = 2 (bf16 gradients in 4-element units, rows of an even number of units): the partial pass gives a
+// lane two ADJACENT units, so its 8 bf16 values are one 128-bit load (a read-only pass needs 128-bit
+// loads to keep up); the update pass gives a lane units `lane` and `lane + 256` of the group, so its
+// 128-bit accesses to m and p stay lane-contiguous.  Both passes index the partial sums and the step
+// scales by column, so the two unit maps never have to agree.
 // ===========================================================================
-constexpr int kStridedUnroll = 4;  // rows in flight per thread
+constexpr int kStridedLoads = 4;  // units in flight per thread in either pass
 
 struct AmStridedItem {
   const AmSeg* seg;
-  uint64_t row0;       // first row of the chunk
-  uint64_t unit;       // unit index inside a row owned by this lane
+  uint64_t row0;       // first row of the tile
+  uint64_t unit0;      // first unit (inside a row) of the tile's column group
   uint32_t row_chunk;
-  bool lane_on;        // the lane's unit exists
 };
 
-__device__ __forceinline__ AmStridedItem am_strided_decode(AM_TABLE_PARAMS, uint32_t item) {
+template <int CPL>
+__device__ __forceinline__ AmStridedItem am_strided_decode(AM_TABLE_PARAMS, uint32_t item, uint32_t rows_per_item) {
   const uint32_t s = am_find_seg(item_keys, n_segs, item);
   AmStridedItem it;
   it.seg = segs + s;
   const uint32_t local = item - item_keys[s];
   it.row_chunk = local / it.seg->chunks_per_block;
   const uint32_t group = local - it.row_chunk * it.seg->chunks_per_block;
-  it.row0 = (uint64_t)it.row_chunk * kStridedRows;
-  it.unit = (uint64_t)group * kStridedThreads + threadIdx.x;
-  it.lane_on = it.unit < it.seg->units_per_block;
+  it.row0 = (uint64_t)it.row_chunk * rows_per_item;
+  it.unit0 = (uint64_t)group * (kStridedThreads * CPL);
   return it;
 }
 
-template <typename G, int VEC>
+template <typename G, int VEC, int CPL>
 __global__ __launch_bounds__(kStridedThreads) void am_strided_partial(AM_KERNEL_PARAMS, uint32_t n_items,
+                                                                      uint32_t rows_per_item,
                                                                       float* __restrict__ partials) {
+  constexpr int W = VEC * CPL;                 // adjacent columns a lane owns in this pass
+  constexpr int ROWS = kStridedLoads;          // rows in flight (one load of W gradients each)
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
-    const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
+    const AmStridedItem it = am_strided_decode<CPL>(AM_TABLE_ARGS, item, rows_per_item);
     const AmSeg& S = *it.seg;
     const uint64_t rows = S.block_numel, row_len = S.row_len;
+    const uint64_t unit = it.unit0 + (uint64_t)threadIdx.x * CPL;   // CPL adjacent units
+    const bool lane_on = unit < S.units_per_block;                  // rows hold a whole number of CPL-unit groups
+    const uint32_t n_rows = (uint32_t)(rows - it.row0 < rows_per_item ? rows - it.row0 : rows_per_item);
     const uint32_t red = S.reducer;
-    float acc[VEC];
+    float acc[W];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = am_red_identity(red);
-    for (int r = 0; r < kStridedRows; r += kStridedUnroll) {
-      float gv[kStridedUnroll][VEC];
+    for (int j = 0; j < W; ++j) acc[j] = am_red_identity(red);
+    for (uint32_t r = 0; r < n_rows; r += ROWS) {
+      float gv[ROWS][W];
 #pragma unroll
-      for (int q = 0; q < kStridedUnroll; ++q) {
+      for (int q = 0; q < ROWS; ++q) {
         const uint64_t row = it.row0 + r + q;
-        if (it.lane_on && row < rows) {
-          am_load_grad<G, VEC>(S.g, row * row_len + it.unit * VEC, gv[q]);
+        if (lane_on && r + q < n_rows) {
+          am_load_grad<G, W>(S.g, row * row_len + unit * VEC, gv[q]);
         } else {
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) gv[q][j] = 0.0f;
+          for (int j = 0; j < W; ++j) gv[q][j] = 0.0f;
         }
       }
       if (am_red_is_sum_sq(red)) {
 #pragma unroll
-        for (int q = 0; q < kStridedUnroll; ++q)
+        for (int q = 0; q < ROWS; ++q)
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) acc[j] = fmaf(gv[q][j], gv[q][j], acc[j]);
+          for (int j = 0; j < W; ++j) acc[j] = fmaf(gv[q][j], gv[q][j], acc[j]);
       } else {
 #pragma unroll
-        for (int q = 0; q < kStridedUnroll; ++q)
-          if (it.lane_on && it.row0 + r + q < rows) {
+        for (int q = 0; q < ROWS; ++q)
+          if (lane_on && r + q < n_rows) {
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-              const float one[1] = {gv[q][j]};  // a lane's VEC columns are VEC different blocks
+            for (int j = 0; j < W; ++j) {
+              const float one[1] = {gv[q][j]};  // a lane's W columns are W different blocks
               acc[j] = am_red_accumulate(red, one, acc[j]);
             }
           }
       }
     }
     // plain (cached) stores: the finalize kernel reads these back right away
-    if (it.lane_on) {
-      float* dst = partials + S.aux + (uint64_t)it.row_chunk * row_len + it.unit * VEC;
+    if (lane_on) {
+      float* dst = partials + S.aux + (uint64_t)it.row_chunk * row_len + unit * VEC;
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) dst[j] = acc[j];
+      for (int j = 0; j < W; ++j) dst[j] = acc[j];
     }
   }
 }
 
-// One thread per column of the bucket.
+// One thread per column of the bucket; consecutive threads read consecutive floats of a chunk's partials.
 __global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uint32_t n_cols,
+                                                           uint32_t rows_per_item,
                                                            const float* __restrict__ partials,
                                                            float* __restrict__ v, float* __restrict__ scales,
                                                            AmScalars sc) {
@@ -644,13 +687,15 @@ __global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uin
     const AmSeg& S = segs[s];
     const uint64_t col = gc - lblock_keys[s];
     const uint64_t rows = S.block_numel, row_len = S.row_len;
-    const uint64_t n_chunks = (rows + kStridedRows - 1) / kStridedRows;
+    const uint64_t n_chunks = (rows + rows_per_item - 1) / rows_per_item;
+    const float* src = partials + S.aux + col;
     const uint32_t red = S.reducer;
     double acc = (double)am_red_identity(red);
     if (am_red_is_sum_sq(red)) {
-      for (uint64_t c = 0; c < n_chunks; ++c) acc += (double)partials[S.aux + c * row_len + col];
+#pragma unroll 4
+      for (uint64_t c = 0; c < n_chunks; ++c) acc += (double)src[c * row_len];
     } else {
-      for (uint64_t c = 0; c < n_chunks; ++c) acc = am_combine(red, acc, (double)partials[S.aux + c * row_len + col]);
+      for (uint64_t c = 0; c < n_chunks; ++c) acc = am_combine(red, acc, (double)src[c * row_len]);
     }
     const uint64_t v_idx = S.v_first + col;
     float v_new, scale;
@@ -660,65 +705,86 @@ __global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uin
   }
 }
 
-template <typename G, int VEC>
+template <typename G, int VEC, int CPL>
 __global__ __launch_bounds__(kStridedThreads) void am_strided_update(AM_KERNEL_PARAMS, uint32_t n_items,
+                                                                     uint32_t rows_per_item,
                                                                      const float* __restrict__ scales,
                                                                      AmScalars sc) {
+  constexpr int ROWS = kStridedLoads / CPL;    // rows in flight (CPL units each)
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
-    const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
+    const AmStridedItem it = am_strided_decode<CPL>(AM_TABLE_ARGS, item, rows_per_item);
     const AmSeg& S = *it.seg;
     const uint64_t rows = S.block_numel, row_len = S.row_len;
     const float decay = sc.lr_wd * S.wd_scale;
-    float scale[VEC];
+    const uint32_t n_rows = (uint32_t)(rows - it.row0 < rows_per_item ? rows - it.row0 : rows_per_item);
+    uint64_t unit[CPL];
+    bool on[CPL];
+    float scale[CPL][VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) scale[j] = 0.0f;
-    if (it.lane_on) {
-      const float* src = scales + S.lblock_first + it.unit * VEC;
+    for (int c = 0; c < CPL; ++c) {
+      unit[c] = it.unit0 + threadIdx.x + (uint64_t)c * kStridedThreads;
+      on[c] = unit[c] < S.units_per_block;
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) scale[j] = src[j];
+      for (int j = 0; j < VEC; ++j) scale[c][j] = 0.0f;
+      if (on[c]) {
+        const float* src = scales + S.lblock_first + unit[c] * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) scale[c][j] = src[j];
+      }
     }
-    for (int r = 0; r < kStridedRows; r += kStridedUnroll) {
-      float gv[kStridedUnroll][VEC], mv[kStridedUnroll][VEC], pv[kStridedUnroll][VEC];
+    for (uint32_t r = 0; r < n_rows; r += ROWS) {
+      float gv[ROWS][CPL][VEC], mv[ROWS][CPL][VEC], pv[ROWS][CPL][VEC];
 #pragma unroll
-      for (int q = 0; q < kStridedUnroll; ++q) {
+      for (int q = 0; q < ROWS; ++q) {
         const uint64_t row = it.row0 + r + q;
-        if (it.lane_on && row < rows) {
-          const uint64_t e = row * row_len + it.unit * VEC;
-          am_load_grad<G, VEC>(S.g, e, gv[q]);
-          am_load_f32<VEC>(S.m, e, mv[q]);
-          am_load_f32<VEC>(S.p, e, pv[q]);
-        }
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+          if (on[c] && r + q < n_rows) {
+            const uint64_t e = row * row_len + unit[c] * VEC;
+            am_load_grad<G, VEC>(S.g, e, gv[q][c]);
+            am_load_f32<VEC>(S.m, e, mv[q][c]);
+            am_load_f32<VEC>(S.p, e, pv[q][c]);
+          }
       }
 #pragma unroll
-      for (int q = 0; q < kStridedUnroll; ++q) {
+      for (int q = 0; q < ROWS; ++q) {
         const uint64_t row = it.row0 + r + q;
-        if (it.lane_on && row < rows) {
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) am_update_elem(gv[q][j], mv[q][j], pv[q][j], scale[j], decay, sc);
-          const uint64_t e = row * row_len + it.unit * VEC;
-          am_store_f32<VEC>(S.m, e, mv[q]);
-          am_store_f32<VEC>(S.p, e, pv[q]);
-        }
+        for (int c = 0; c < CPL; ++c)
+          if (on[c] && r + q < n_rows) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+              am_update_elem(gv[q][c][j], mv[q][c][j], pv[q][c][j], scale[c][j], decay, sc);
+            const uint64_t e = row * row_len + unit[c] * VEC;
+            am_store_f32<VEC>(S.m, e, mv[q][c]);
+            am_store_f32<VEC>(S.p, e, pv[q][c]);
+          }
       }
     }
   }
 }
 
-template <int VEC>
+template <int VEC, int CPL>
 __global__ __launch_bounds__(kStridedThreads) void am_strided_ids(AM_KERNEL_PARAMS, uint32_t n_items,
-                                                                  uint32_t tensor, uint64_t* __restrict__ ids) {
+                                                                  uint32_t rows_per_item, uint32_t tensor,
+                                                                  uint64_t* __restrict__ ids) {
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
-    const AmStridedItem it = am_strided_decode(AM_TABLE_ARGS, item);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
+    const AmStridedItem it = am_strided_decode<CPL>(AM_TABLE_ARGS, item, rows_per_item);
     const AmSeg& S = *it.seg;
-    if (S.tensor != tensor || !it.lane_on) continue;
-    for (int r = 0; r < kStridedRows; ++r) {
-      const uint64_t row = it.row0 + r;
-      if (row < S.block_numel) {
-        const uint64_t e = row * S.row_len + it.unit * VEC;
+    if (S.tensor != tensor) continue;
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) ids[e + j] = S.v_first + it.unit * VEC + j;
+    for (int c = 0; c < CPL; ++c) {
+      const uint64_t unit = it.unit0 + threadIdx.x + (uint64_t)c * kStridedThreads;   // the update pass's unit map
+      if (unit >= S.units_per_block) continue;
+      for (uint32_t r = 0; r < rows_per_item; ++r) {
+        const uint64_t row = it.row0 + r;
+        if (row < S.block_numel) {
+          const uint64_t e = row * S.row_len + unit * VEC;
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) ids[e + j] = S.v_first + unit * VEC + j;
+        }
       }
     }
   }
@@ -744,7 +810,7 @@ template <typename G, int VEC, int THREADS, int UPT>
 __global__ __launch_bounds__(THREADS) void am_elementwise(AM_KERNEL_PARAMS,
                                                           uint32_t n_items, float* __restrict__ v, AmScalars sc) {
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
     const AmTileItem it = am_tile_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     float* __restrict__ vt = v + S.v_first;
@@ -787,7 +853,7 @@ __global__ __launch_bounds__(THREADS) void am_elementwise_ids(AM_KERNEL_PARAMS,
                                                               uint32_t n_items, uint32_t tensor,
                                                               uint64_t* __restrict__ ids) {
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_shift);
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
     const AmTileItem it = am_tile_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     if (S.tensor != tensor) continue;

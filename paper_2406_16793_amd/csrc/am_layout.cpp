@@ -47,7 +47,7 @@ bool lanes_allowed(int lanes, uint64_t units, const AmTuning& t) {
 }
 
 bool same_variant(const AmVariant& a, const AmVariant& b) {
-  return a.family == b.family && a.vec == b.vec && a.lanes == b.lanes && a.upt == b.upt;
+  return a.family == b.family && a.vec == b.vec && a.lanes == b.lanes && a.upt == b.upt && a.aux == b.aux;
 }
 
 }  // namespace
@@ -139,7 +139,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     // Column blocks of a [block_numel, n_blocks] matrix.  With one column the block is the whole
     // (contiguous) tensor and with one row every element is its own block: both are plain layouts.
     ti.strided = (d.flags & ADAM_MINI_FLAG_STRIDED) != 0 && ti.n_blocks > 1 && d.block_numel > 1;
-    AmVariant var;
+    AmVariant var{};
     if (ti.strided) {
       const int native = grad_dtype == ADAM_MINI_GRAD_BF16 ? (tuning.bf16_vec == 8 ? 8 : 4) : 4;
       var.family = AM_FAM_STRIDED;
@@ -147,7 +147,10 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       // so the tensor's v slice needs no alignment of its own)
       var.vec = (ti.n_blocks % (uint64_t)native == 0) ? native : 1;
       var.lanes = 256;
-      var.upt = kStridedRows;
+      var.upt = (int)tuning.strided_rows;
+      // bf16 gradients in 4-element units: two units per lane where every row holds whole pairs, so that the
+      // read-only partial pass can take a lane's 8 gradients in one 128-bit load
+      var.aux = (grad_dtype == ADAM_MINI_GRAD_BF16 && var.vec == 4 && ti.n_blocks % 8 == 0) ? 2 : 1;
     } else {
       var = am_choose_variant(grad_dtype, d.numel, d.block_numel, ti.v_first, tuning);
     }
@@ -184,8 +187,9 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       const uint64_t rows = d.block_numel, cols = ti.n_blocks;
       s.row_len = cols;
       s.units_per_block = cols / (uint64_t)var.vec;                        // units per stored row
-      const uint64_t groups = (s.units_per_block + kStridedThreads - 1) / kStridedThreads;  // column groups
-      const uint64_t row_chunks = (rows + kStridedRows - 1) / kStridedRows;                 // rows per work item
+      const uint64_t group_units = (uint64_t)kStridedThreads * (uint64_t)var.aux;
+      const uint64_t groups = (s.units_per_block + group_units - 1) / group_units;          // column groups
+      const uint64_t row_chunks = (rows + (uint64_t)var.upt - 1) / (uint64_t)var.upt;       // tiles along the rows
       if (groups >= (1ull << 31) || cols >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
       s.chunks_per_block = (uint32_t)groups;
       s.aux = bk.n_partials;                                               // partial sums: [row_chunks][cols]

@@ -54,6 +54,9 @@ struct AmTuning {
   int64_t row_blocked = 0;          // 1: each wavefront of a row team owns a contiguous span of the block
   int64_t strided_wg_per_cu = 4;    // > 0: cap on resident workgroups per compute unit of the column-block update kernel
   int64_t stream_wg_per_cu = 2;     // > 0: same for the elementwise / large-update streaming kernels
+  int64_t strided_rows = 64;        // column-block kernels: rows of the stored matrix per work item (multiple of 4)
+  int64_t xcd_count = 8;            // XCDs the hardware deals workgroups to round-robin (power of two; 8 when the
+                                    //   device is one partition)
   int64_t xcd_chunk = 64;           // row kernels: consecutive workgroup passes one XCD walks (power of two; 0 = the
                                     //   hardware's round-robin order, item by item)
   int64_t xcd_chunk_stream = 16;    // same for the elementwise and large-block kernels

@@ -15,7 +15,7 @@ enum AmFamily : int {
   AM_FAM_ROW = 1,          // item = one block, held in the registers of a team of LANES threads
   AM_FAM_LARGE = 2,        // item = one chunk of a block; partial sums + finalize + update
   AM_FAM_ROW_LDS = 3,      // item = one block, gradient staged in the workgroup's LDS
-  AM_FAM_STRIDED = 4       // blocks are columns: item = (row chunk, group of 256 column units)
+  AM_FAM_STRIDED = 4       // blocks are columns: item = (row chunk, group of 256 or 512 column units)
 };
 
 // One tensor inside one bucket.  Device pointers are filled in at step time.
@@ -46,13 +46,14 @@ struct AmTable {
   const uint32_t* item_keys;    // [n_segs] ascending
   const uint32_t* lblock_keys;  // [n_segs] ascending (LARGE only; otherwise zeros)
   uint32_t n_segs;
-  uint32_t xcd_shift;           // log2 of the run of work-item groups one XCD walks; >= 32: identity order
+  uint32_t xcd_code;            // low byte: log2 of the run of work-item groups one XCD walks (>= 32: identity
+                                // order); next byte: log2 of the number of XCDs
 };
 
 // Tile of the STRIDED family, shared by the layout builder and the kernels: a workgroup of
-// kStridedThreads lanes owns kStridedThreads units of a row over kStridedRows consecutive rows.
+// kStridedThreads lanes owns kStridedThreads * aux units of a row (aux = AmVariant::aux, 1 or 2) over
+// AmVariant::upt consecutive rows.
 constexpr int kStridedThreads = 256;
-constexpr int kStridedRows = 16;
 
 // Per-step scalars, computed on the host in double and rounded once to fp32.
 struct AmScalars {
@@ -71,7 +72,8 @@ struct AmVariant {
   int family;  // AmFamily
   int vec;     // elements per unit: 1 (scalar fallback), 4 (fp32 grads) or 8 (bf16 grads)
   int lanes;   // threads cooperating on one item
-  int upt;     // units per thread (compile-time unroll)
+  int upt;     // units per thread (compile-time unroll); STRIDED: rows per work item (a launch argument)
+  int aux;     // STRIDED: units of a row per lane (1 or 2); otherwise 0
 };
 
 #endif  // AM_TABLES_H_

@@ -17,3 +17,21 @@ def oracle():
     import oracle as _oracle
     _oracle.build()
     return _oracle
+
+
+@pytest.fixture
+def say(capsys):
+    """Progress lines that reach the real stdout at once (capture switched off for the print) and a
+    log file under gpurun_out/: a long full-size test must not look hung."""
+    log = os.path.join(ROOT, "gpurun_out", "fullsize_progress.log")
+
+    def _say(msg):
+        with capsys.disabled():
+            print("\n[fullsize] " + msg, flush=True)
+        try:
+            os.makedirs(os.path.dirname(log), exist_ok=True)
+            with open(log, "a") as f:
+                f.write(msg + "\n")
+        except OSError:
+            pass
+    return _say

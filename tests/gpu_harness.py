@@ -11,10 +11,23 @@ from paper_2406_16793_amd.device_state import DeviceState as GpuRun, grad_to_hos
 from paper_2406_16793_amd.partition import TensorSpec
 
 
-def assert_state_close(name, got, want, rtol, is_v=False):
-    """Elementwise bound  |got - want| <= rtol*|want| + rtol*rms(want)  for p and m (rms over
-    the tensor's finite entries), and  <= rtol*|want| + 1e-30  for v.  Non-finite entries
-    must coincide.  Returns the normwise relative error over the finite entries."""
+# Every comparison is held to this relative tolerance, whatever the gradient type: both sides get the same
+# bf16 bit patterns, so bf16 runs are as exact as fp32 ones.  The 5e-3 a bf16 workload carries in `rtol`
+# is the contract's ceiling; it is reported, never relied on.
+TIGHT_RTOL = 1e-5
+
+
+def check_rtol(rtol):
+    return min(float(rtol), TIGHT_RTOL)
+
+
+def assert_state_close(name, got, want, rtol, is_v=False, block_numel=None, strided=False):
+    """Elementwise bound  |got - want| <= rtol*|want| + rtol*rms  for p and m, where rms is taken over
+    the finite entries of the element's own BLOCK when block_numel is given (contiguous runs, or the
+    columns of the row-major [block_numel, n_blocks] array if strided), else over the whole array;
+    and  <= rtol*|want| + 1e-30  for v.  rtol is capped at TIGHT_RTOL.  Non-finite entries must
+    coincide.  Returns the normwise relative error over the finite entries."""
+    rtol = check_rtol(rtol)
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, name
@@ -25,6 +38,11 @@ def assert_state_close(name, got, want, rtol, is_v=False):
         d = np.where(ok, got - want, 0.0)
     if is_v:
         tol = rtol * np.abs(w) + 1e-30
+    elif block_numel is not None and block_numel > 1 and w.size % block_numel == 0:
+        shape, axis = ((block_numel, w.size // block_numel), 0) if strided else ((w.size // block_numel, block_numel), 1)
+        w2, ok2 = w.reshape(shape), ok.reshape(shape)
+        rms = np.sqrt(np.sum(np.square(w2), axis=axis, keepdims=True) / np.maximum(1, ok2.sum(axis=axis, keepdims=True)))
+        tol = (rtol * np.abs(w2) + rtol * rms).reshape(-1)
     else:
         rms = float(np.sqrt(np.sum(np.square(w)) / max(1, int(ok.sum()))))
         tol = rtol * np.abs(w) + rtol * rms
@@ -94,14 +112,15 @@ def compare(run: GpuRun, st: orc.OracleState, rtol: float, label="") -> float:
     off = 0
     for k, s in enumerate(run.specs):
         nb = s.numel // s.block_numel
-        worst = max(worst, assert_state_close("%s param[%d] %s" % (label, k, s.name), run.p[k].cpu().numpy(), st.p[k], rtol))
-        worst = max(worst, assert_state_close("%s m[%d] %s" % (label, k, s.name), run.m[k].cpu().numpy(), st.m[k], rtol))
+        bn = dict(block_numel=s.block_numel, strided=s.strided)
+        worst = max(worst, assert_state_close("%s param[%d] %s" % (label, k, s.name), run.p[k].cpu().numpy(), st.p[k], rtol, **bn))
+        worst = max(worst, assert_state_close("%s m[%d] %s" % (label, k, s.name), run.m[k].cpu().numpy(), st.m[k], rtol, **bn))
         worst = max(worst, assert_state_close("%s v[%d] %s" % (label, k, s.name), v[off:off + nb], st.v[k], rtol, is_v=True))
         off += nb
     return worst
 
 
-def sample_blocks(wl, per_tensor=6, large_per_tensor=2, seed=1234, giant_budget=200_000_000):
+def sample_blocks(wl, per_tensor=16, large_per_tensor=3, seed=1234, giant_budget=200_000_000):
     """Seeded choice of block indices per tensor: first, last and random ones; fewer for blocks
     above 64K elements (attention heads) so the oracle finishes in seconds.  Blocks above 4 M
     elements (whole-tensor partitions) are sampled one per tensor, in a seeded order, until
@@ -129,7 +148,7 @@ def sample_blocks(wl, per_tensor=6, large_per_tensor=2, seed=1234, giant_budget=
     return picks
 
 
-def run_sampled(wl: workloads.Workload, steps=None, per_tensor=6, large_per_tensor=2, progress=None):
+def run_sampled(wl: workloads.Workload, steps=None, per_tensor=16, large_per_tensor=3, progress=None):
     """Full-size run on the GPU (the launch configuration the benchmark times); the oracle
     follows only a seeded sample of whole blocks, which is exact because blocks never interact.
     Returns (DeviceState, worst normwise relative error over the sampled blocks)."""
@@ -176,8 +195,82 @@ def run_sampled(wl: workloads.Workload, steps=None, per_tensor=6, large_per_tens
     for j, k in enumerate(active):
         s = wl.specs[k]
         name = "%s[%d] %s" % (wl.name, k, s.name)
-        worst = max(worst, assert_state_close("param " + name, gather(run.p, k).cpu().numpy().reshape(-1), st.p[j], wl.rtol))
-        worst = max(worst, assert_state_close("m " + name, gather(run.m, k).cpu().numpy().reshape(-1), st.m[j], wl.rtol))
+        # the gathered blocks are contiguous rows for both layouts
+        worst = max(worst, assert_state_close("param " + name, gather(run.p, k).cpu().numpy().reshape(-1), st.p[j], wl.rtol,
+                                              block_numel=s.block_numel))
+        worst = max(worst, assert_state_close("m " + name, gather(run.m, k).cpu().numpy().reshape(-1), st.m[j], wl.rtol,
+                                              block_numel=s.block_numel))
         vk = v[int(v_first[k]):int(v_first[k + 1])][dev_picks[k]].cpu().numpy()
         worst = max(worst, assert_state_close("v " + name, vk, st.v[j], wl.rtol, is_v=True))
     return run, worst
+
+
+def record_error(workload: str, mode: str, worst: float, elements: int, steps: int) -> None:
+    """Keeps the worst normwise relative error of a full-size comparison in gpurun_out/fullsize_errors.json
+    (merged per workload and mode), so the figures survive a quiet pytest run."""
+    import json
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    path = os.path.join(root, "gpurun_out", "fullsize_errors.json")
+    try:
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+        data = json.load(open(path)) if os.path.exists(path) else {}
+        data["%s/%s" % (workload, mode)] = {"worst_normwise_rel_err": worst, "elements_compared": int(elements),
+                                            "steps": int(steps), "asserted_below": TIGHT_RTOL}
+        with open(path, "w") as f:
+            json.dump(data, f, indent=1, sort_keys=True)
+    except OSError:
+        pass
+
+
+def run_complete(wl: workloads.Workload, steps=None, tensors=None, progress=None, row_chunk=8192):
+    """Full-size run on the GPU over ALL tensors of `wl` (the launch configuration the benchmark times),
+    then the oracle streamed tensor by tensor: for each tensor in `tensors` (default: every one) the
+    initial values and the gradient of every step are generated again from their seeds, the oracle steps
+    that whole tensor on the host, and every element of p and m and every v of the tensor is compared.
+    The regenerated last-step gradient must equal, bit for bit, the one still resident on the GPU.
+    Returns (DeviceState, worst normwise relative error, elements compared)."""
+    import torch
+    steps = wl.steps if steps is None else steps
+    todo = list(range(len(wl.specs))) if tensors is None else list(tensors)
+    run = GpuRun(wl.specs, wl.grad_dtype)
+    hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
+    ohp = orc.Hyper.from_f32(**hp)
+    for k, s in enumerate(wl.specs):
+        run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
+    for t in range(1, steps + 1):
+        for k, s in enumerate(wl.specs):
+            workloads.fill_grad(run.g[k], s, wl, k, t, row_chunk=row_chunk)
+        run.opt.step(step=t, **hp)
+        if progress:
+            torch.cuda.synchronize()
+            progress("gpu step %d/%d done" % (t, steps))
+    torch.cuda.synchronize()
+    v_first = np.concatenate([[0], np.cumsum([s.n_blocks for s in wl.specs])])
+    gdt = workloads.torch_grad_dtype(wl)
+    worst, compared, since = 0.0, 0, 0
+    for i, k in enumerate(todo):
+        s = wl.specs[k]
+        p0 = workloads.init_param(s, wl.seed, k, device=run.dev).cpu().numpy()
+        st = orc.OracleState([s.numel], [s.block_numel], [s.wd_scale], [p0], strided=[s.strided], reducer=[s.reducer])
+        del p0
+        tmp = torch.empty(s.numel, dtype=gdt, device=run.dev)
+        for t in range(1, steps + 1):
+            workloads.fill_grad(tmp, s, wl, k, t, row_chunk=row_chunk)
+            if t == steps:
+                assert torch.equal(tmp, run.g[k]), "regenerated gradient of tensor %d differs from the resident one" % k
+            st.step([grad_to_host(tmp)], ohp)
+        del tmp
+        name = "%s[%d] %s" % (wl.name, k, s.name)
+        bn = dict(block_numel=s.block_numel, strided=s.strided)
+        worst = max(worst, assert_state_close("param " + name, run.p[k].cpu().numpy(), st.p[0], wl.rtol, **bn))
+        worst = max(worst, assert_state_close("m " + name, run.m[k].cpu().numpy(), st.m[0], wl.rtol, **bn))
+        vk = run.v[int(v_first[k]):int(v_first[k + 1])].cpu().numpy()
+        worst = max(worst, assert_state_close("v " + name, vk, st.v[0], wl.rtol, is_v=True))
+        compared += 2 * s.numel + s.n_blocks
+        since += s.numel
+        del st
+        if progress and (since >= 400_000_000 or i + 1 == len(todo)):
+            progress("oracle: %d of %d tensors compared, worst normwise rel err so far %.3g" % (i + 1, len(todo), worst))
+            since = 0
+    return run, worst, compared

@@ -261,3 +261,4 @@ def test_reducer_flags_are_validated():
     for bad in (5 << 4, 7 << 4, 1 << 7, 1 << 1, 1 << 3):
         with pytest.raises(B.AdamMiniError):
             B.adam_mini_init_layout([(4096, 4096, 1.0, bad)], B.GRAD_F32, -1)
+

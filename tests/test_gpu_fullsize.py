@@ -1,17 +1,52 @@
 """Full-size configurations on the GPU, in the launch configuration bench.py times.
-The oracle follows a seeded sample of whole blocks of every tensor (blocks never
-interact, so each sampled block is compared exactly as if the oracle had run the
-whole set), and size-independent properties are checked on everything."""
-import sys
 
+Complete set: the Llama-2-7B configuration (the one the metric is quoted on) is stepped whole on the
+GPU and then every tensor is streamed through the oracle, every element compared.  For the two larger
+configurations the embedding, the output layer, the first and the last transformer layer and the final
+norm are compared completely.  Besides that the oracle follows a seeded sample of whole blocks of every
+tensor of every configuration (blocks never interact, so each sampled block is compared exactly as if
+the oracle had run the whole set), and size-independent properties are checked on everything.  Every
+comparison asserts a normwise relative error below 1e-5 next to the elementwise bound, and leaves its
+worst figure in gpurun_out/fullsize_errors.json."""
 import pytest
 
 pytestmark = pytest.mark.gpu
 
 
-def _say(msg):
-    print(msg, flush=True)
-    sys.stdout.flush()
+def _fits(torch, need):
+    return torch.cuda.get_device_properties(0).total_memory >= need
+
+
+def _edge_tensors(wl):
+    """Embedding, output layer, first and last transformer layer, final norm."""
+    layers = sorted({int(s.name.split(".")[1]) for s in wl.specs if s.name.startswith("layers.")})
+    first, last = "layers.%d." % layers[0], "layers.%d." % layers[-1]
+    return [k for k, s in enumerate(wl.specs)
+            if s.name.startswith(("embed", "output", "final_norm", first, last))]
+
+
+@pytest.mark.parametrize("name,steps,subset", [("llama2_7b", 10, "all"), ("llama3_8b", 10, "edges"), ("llama2_13b", 5, "edges")])
+def test_full_size_complete_set(name, steps, subset, say):
+    """Every element of every compared tensor after the configuration's full number of steps."""
+    import gpu_harness as H
+    import torch
+    from paper_2406_16793_amd import workloads
+    wl = workloads.get(name)
+    need = wl.n_params * (10 if wl.grad_dtype == "bf16" else 12) + (8 << 30)
+    if not _fits(torch, need):
+        pytest.skip("needs %.0f GB of device memory" % (need / 1e9))
+    tensors = None if subset == "all" else _edge_tensors(wl)
+    n = wl.n_params if tensors is None else sum(wl.specs[k].numel for k in tensors)
+    say("%s complete: %d of %d tensors, %d params compared elementwise, %d steps"
+        % (name, len(wl.specs) if tensors is None else len(tensors), len(wl.specs), n, steps))
+    run, worst, compared = H.run_complete(wl, steps=steps, tensors=tensors, progress=say)
+    say("%s complete: worst normwise rel err %.3g over %d values" % (name, worst, compared))
+    H.record_error(name, "complete_" + subset, worst, compared, steps)
+    assert worst < H.TIGHT_RTOL
+    _check_global_properties(run, wl)
+    run.close()
+    del run
+    torch.cuda.empty_cache()
 
 
 def _check_global_properties(run, wl):
@@ -30,7 +65,7 @@ def _check_global_properties(run, wl):
 
 @pytest.mark.parametrize("name,steps", [("llama2_7b", 10), ("llama3_8b", 10), ("llama2_13b", 5), ("llama2_7b_value_whole", 3),
                                         ("llama2_7b_embed_t", 3), ("llama2_7b_whole", 2)])
-def test_full_size_sampled_blocks(name, steps):
+def test_full_size_sampled_blocks(name, steps, say):
     import gpu_harness as H
     import torch
     from paper_2406_16793_amd import workloads
@@ -39,16 +74,18 @@ def test_full_size_sampled_blocks(name, steps):
     total = torch.cuda.get_device_properties(0).total_memory
     if total < need:
         pytest.skip("needs %.0f GB of device memory, have %.0f GB" % (need / 1e9, total / 1e9))
-    _say("%s: %d params, %d blocks, %d steps" % (name, wl.n_params, wl.n_blocks, steps))
-    run, worst = H.run_sampled(wl, steps=steps, progress=_say)
-    _say("%s: worst normwise rel err over sampled blocks %.3g" % (name, worst))
+    say("%s: %d params, %d blocks, %d steps" % (name, wl.n_params, wl.n_blocks, steps))
+    run, worst = H.run_sampled(wl, steps=steps, progress=say)
+    say("%s: worst normwise rel err over sampled blocks %.3g" % (name, worst))
+    H.record_error(name, "sampled", worst, 0, steps)
+    assert worst < H.TIGHT_RTOL
     _check_global_properties(run, wl)
     run.close()
     del run
     torch.cuda.empty_cache()
 
 
-def test_full_size_adamw_equivalent_mode():
+def test_full_size_adamw_equivalent_mode(say):
     """Llama-2-7B shape with every block of size 1 (dense v, 26 bytes per parameter): sampled elements."""
     import gpu_harness as H
     import torch
@@ -59,8 +96,10 @@ def test_full_size_adamw_equivalent_mode():
     need = wl.n_params * 14 + (6 << 30)
     if torch.cuda.get_device_properties(0).total_memory < need:
         pytest.skip("needs %.0f GB of device memory" % (need / 1e9))
-    run, worst = H.run_sampled(wl, steps=3, progress=_say)
-    _say("llama2_7b_adamw: worst normwise rel err over sampled elements %.3g" % worst)
+    run, worst = H.run_sampled(wl, steps=3, progress=say)
+    say("llama2_7b_adamw: worst normwise rel err over sampled elements %.3g" % worst)
+    H.record_error(wl.name, "sampled", worst, 0, 3)
+    assert worst < H.TIGHT_RTOL
     assert bool(torch.isfinite(run.v).all()) and float(run.v.min()) >= 0.0
     run.close()
     del run
@@ -68,7 +107,7 @@ def test_full_size_adamw_equivalent_mode():
 
 
 @pytest.mark.parametrize("kind", ["rows", "adamw", "columns"])
-def test_tensor_beyond_2_to_32_elements(kind):
+def test_tensor_beyond_2_to_32_elements(kind, say):
     """One tensor of more than 2^32 elements (17 GB of fp32 parameters): element offsets are 64-bit in every
     kernel family that can hold such a tensor.  The sample always holds the first and the last block, the
     last one lying wholly above element 2^32."""
@@ -88,9 +127,10 @@ def test_tensor_beyond_2_to_32_elements(kind):
     need = big.numel * (14 if kind == "adamw" else 10) + (24 << 30)      # + the fp32 slab of the gradient generator
     if torch.cuda.get_device_properties(0).total_memory < need:
         pytest.skip("needs %.0f GB of device memory" % (need / 1e9))
-    _say("%s: %d elements in one tensor" % (wl.name, big.numel))
-    run, worst = H.run_sampled(wl, steps=2, progress=_say)
-    _say("%s: worst normwise rel err over sampled blocks %.3g" % (wl.name, worst))
+    say("%s: %d elements in one tensor" % (wl.name, big.numel))
+    run, worst = H.run_sampled(wl, steps=2, progress=say)
+    say("%s: worst normwise rel err over sampled blocks %.3g" % (wl.name, worst))
+    H.record_error(wl.name, "sampled", worst, 0, 2)
     assert worst < 1e-5
     assert bool(torch.isfinite(run.p[1][-8192:]).all()) and float(run.m[1][-8192:].abs().max()) > 0.0
     run.close()
@@ -98,7 +138,7 @@ def test_tensor_beyond_2_to_32_elements(kind):
     torch.cuda.empty_cache()
 
 
-def test_full_size_alternative_block_statistics():
+def test_full_size_alternative_block_statistics(say):
     """Llama-2-7B shape with the ablation's block statistics spread over the tensors (tensor k takes
     statistic k mod 5, so every kernel family meets every statistic): sampled blocks against the oracle."""
     import gpu_harness as H
@@ -113,8 +153,9 @@ def test_full_size_alternative_block_statistics():
     need = wl.n_params * 10 + (6 << 30)
     if torch.cuda.get_device_properties(0).total_memory < need:
         pytest.skip("needs %.0f GB of device memory" % (need / 1e9))
-    run, worst = H.run_sampled(wl, steps=3, progress=_say)
-    _say("%s: worst normwise rel err over sampled blocks %.3g" % (wl.name, worst))
+    run, worst = H.run_sampled(wl, steps=3, progress=say)
+    say("%s: worst normwise rel err over sampled blocks %.3g" % (wl.name, worst))
+    H.record_error(wl.name, "sampled", worst, 0, 3)
     assert worst < 1e-5
     assert bool(torch.isfinite(run.v).all()) and float(run.v.min()) >= 0.0
     run.close()

@@ -529,3 +529,48 @@ def test_random_layouts(seed, oracle):
         torch.cuda.synchronize()
         assert np.array_equal(got.cpu().numpy(), oracle.block_ids_tensor(numel, bnum, k, strided).astype(np.int64))
     run.close()
+
+
+def test_moving_gradient_buffers_cost_no_host_wait():
+    """A framework that hands over different gradient buffers every step: the new pointers reach the
+    device tables as kernel arguments on the step's stream, so (i) 50 steps alternating between two
+    buffer sets give the bits of the same steps on fixed buffers, and (ii) the host has enqueued all 50
+    long before the device has run them (the call never waits for the stream)."""
+    import gpu_harness as H
+    import torch
+    # ~0.5 ms of device time per step, against some 0.1 ms of host time to enqueue one
+    shapes = [(32768, 4096), (4, 524288), (3, 49152), (700, 64), (5000, 1), (7, 333)]
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    wl = _wl(shapes, "bf16")
+    specs = wl.specs + H.make_specs([(1024, 96)], strided=True)
+    fixed, moving = H.GpuRun(specs, "bf16"), H.GpuRun(specs, "bf16")
+    torch.manual_seed(9)
+    sets = [[(torch.randn(s.numel) * 1e-3).to(torch.bfloat16).cuda() for s in specs] for _ in range(2)]
+    for k, s in enumerate(specs):
+        p0 = torch.randn(s.numel) * 0.02
+        fixed.p[k].copy_(p0)
+        moving.p[k].copy_(p0)
+    # reference: one fixed set of buffers, contents swapped by copies
+    for t in range(1, 51):
+        for k in range(len(specs)):
+            fixed.g[k].copy_(sets[t % 2][k])
+        fixed.opt.step(step=t, **hp)
+    torch.cuda.synchronize()
+    # moving pointers: two warm-up calls (the first one creates the device tables), then 50 steps enqueued at once
+    moving.opt.bind(moving.p, sets[1], moving.m, moving.v)
+    stream = torch.cuda.current_stream()
+    done = torch.cuda.Event()
+    for t in range(1, 51):
+        moving.opt.bind(moving.p, sets[t % 2], moving.m, moving.v)
+        moving.opt.step(step=t, **hp)
+        if t == 1:
+            torch.cuda.synchronize()          # table creation (blocking by contract) is behind us
+    done.record(stream)
+    still_running = not done.query()          # the device is far from finished when the last call returns
+    torch.cuda.synchronize()
+    for k in range(len(specs)):
+        assert torch.equal(fixed.p[k], moving.p[k]) and torch.equal(fixed.m[k], moving.m[k]), k
+    assert torch.equal(fixed.v, moving.v)
+    assert still_running, "the host waited for the stream inside adam_mini_step"
+    fixed.close()
+    moving.close()

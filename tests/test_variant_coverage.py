@@ -32,7 +32,9 @@ def _launchable():
             out |= {(FAM_EW, grad, vec, l, u) for l, u in ew}
             if vec > 1:
                 out.add((FAM_ROW_LDS, grad, vec, 1024, 1))
-            out.add((FAM_STRIDED, grad, vec, 256, 0))
+            out.add((FAM_STRIDED, grad, vec, 256, 1))
+            if grad == "bf16" and vec == 4:
+                out.add((FAM_STRIDED, grad, vec, 256, 2))          # two units of a row per lane
     return out
 
 
@@ -48,7 +50,10 @@ def test_variant_cases_reach_every_kernel_instantiation():
                     B.adam_mini_set_option(k, v)
                 h = B.adam_mini_init_layout(descs, B.GRAD_BF16 if grad == "bf16" else B.GRAD_F32, -1)
                 for b in B.adam_mini_profile_read(h):
-                    upt = 0 if b["family"] == FAM_STRIDED else b["upt"]    # column blocks: upt holds the tile height
+                    upt = b["upt"]
+                    if b["family"] == FAM_STRIDED:      # upt holds the tile height (a launch argument); the template
+                        upt = int(b["kernel"].rstrip(">").split(",")[-1])   # argument is the units per lane
+
                     reached.add((b["family"], grad, b["vec"], b["lanes"], upt))
                 B.adam_mini_destroy_layout(h)
     finally:

@@ -88,6 +88,15 @@ CASES = [
     ("stream_wg_per_cu=8", _o(stream_wg_per_cu=8), ("bf16",)),
     ("strided_wg_per_cu=0", _o(strided_wg_per_cu=0), ("bf16",)),
     ("strided_wg_per_cu=1", _o(strided_wg_per_cu=1), ("f32",)),
+    ("strided_rows=4", _o(strided_rows=4), BOTH),
+    ("strided_rows=16", _o(strided_rows=16), ("bf16",)),
+    ("strided_rows=20", _o(strided_rows=20), BOTH),
+    ("strided_rows=256", _o(strided_rows=256), ("f32",)),
+    ("strided_rows=4096-vec8", _o(strided_rows=4096, bf16_vec=8), ("bf16",)),
+    ("xcd_count=1", _o(xcd_count=1, xcd_chunk=2, xcd_chunk_stream=2, xcd_chunk_strided=2), ("bf16",)),
+    ("xcd_count=2", _o(xcd_count=2, xcd_chunk=2, xcd_chunk_stream=4, xcd_chunk_strided=1), ("f32",)),
+    ("xcd_count=4", _o(xcd_count=4, xcd_chunk=4, xcd_chunk_stream=2, xcd_chunk_strided=2), ("bf16",)),
+    ("xcd_count=16", _o(xcd_count=16, xcd_chunk=1, xcd_chunk_stream=1, xcd_chunk_strided=1), ("f32",)),
     ("xcd_chunks=1", _o(xcd_chunk=1, xcd_chunk_stream=1, xcd_chunk_strided=1), ("bf16",)),
     ("xcd_chunks=0", _o(xcd_chunk=0, xcd_chunk_stream=0, xcd_chunk_strided=0), ("f32",)),
 ]
