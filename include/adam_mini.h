@@ -48,7 +48,9 @@ typedef enum adam_mini_status {
   ADAM_MINI_MISALIGNED = -2,    /* a device base pointer is not 16-byte aligned */
   ADAM_MINI_OUT_OF_MEMORY = -3, /* host or device allocation failed */
   ADAM_MINI_HIP_ERROR = -4,     /* a HIP runtime call failed (see adam_mini_last_hip_error) */
-  ADAM_MINI_NO_DEVICE = -5      /* the layout was built with device < 0 (host-only layout) */
+  ADAM_MINI_NO_DEVICE = -5,     /* the layout was built with device < 0 (host-only layout) */
+  ADAM_MINI_TOO_LARGE = -6      /* adam_mini_step_static: the layout's work tables and scratch exceed
+                                   ADAM_MINI_STATIC_SCRATCH_BYTES */
 } adam_mini_status;
 
 /* Gradient element type.  Params, exp_avg (m) and v are always fp32. */
@@ -191,6 +193,33 @@ int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor,
 int adam_mini_step(adam_mini_layout* layout, void* const* params,
                    const void* const* grads, void* const* exp_avg, float* v_dev,
                    const adam_mini_hparams* hp, void* hip_stream);
+
+/*
+ * The same step for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results bit for bit, same validation as adam_mini_step; but the work tables,
+ * the partial sums and the step scales live in one fixed array of
+ * ADAM_MINI_STATIC_SCRATCH_BYTES inside the library's code object (every GPU the
+ * library runs on holds its own copy until the process ends), and the tables reach it
+ * as arguments of small kernels on hip_stream.  The call makes no hipMalloc, no
+ * hipFree, no copy and no other allocating call, on its first use or later.
+ * A layout needs  n_tensors * 96 + (partial sums + step scales) * 4  bytes, each part
+ * rounded up to 256 (partial sums: one per 4096-element chunk of every block that
+ * spans several workgroups, or one per column and tile of rows for column blocks);
+ * the five benchmark shapes need 0.1 to 2.1 MB.  ADAM_MINI_TOO_LARGE if it does not
+ * fit; nothing was launched then.
+ * All layouts stepped this way on one GPU share that GPU's array, which keeps the last
+ * call's contents: the tables are rewritten whenever the previous call on the GPU was
+ * another layout's or had other pointers, and every partial sum a step reads is
+ * written earlier in the same step, so nothing needs clearing.  Calls that overlap in
+ * time on one GPU (two streams, two threads) race on the array: order them.
+ * adam_mini_step on the same layout keeps working beside it (it uses the layout's own
+ * allocations).
+ */
+#define ADAM_MINI_STATIC_SCRATCH_BYTES (16u << 20)
+int adam_mini_step_static(adam_mini_layout* layout, void* const* params,
+                          const void* const* grads, void* const* exp_avg, float* v_dev,
+                          const adam_mini_hparams* hp, void* hip_stream);
 
 /*
  * Launch structure and timing.  A step is a short sequence of launches ("buckets"):

@@ -14,7 +14,8 @@ from typing import List, Optional, Sequence, Tuple
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libadam_mini.so")
 
-OK, INVALID_ARG, MISALIGNED, OUT_OF_MEMORY, HIP_ERROR, NO_DEVICE = 0, -1, -2, -3, -4, -5
+OK, INVALID_ARG, MISALIGNED, OUT_OF_MEMORY, HIP_ERROR, NO_DEVICE, TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 16 << 20
 GRAD_F32, GRAD_BF16 = 0, 1
 PATH_ELEMENTWISE, PATH_ROW, PATH_LARGE, PATH_ROW_LDS, PATH_STRIDED = 0, 1, 2, 3, 4
 FLAG_STRIDED = 1
@@ -53,7 +54,7 @@ _lib = None
 
 EXPORTS = ["adam_mini_init_layout", "adam_mini_num_blocks", "adam_mini_num_tensors",
            "adam_mini_export_layout", "adam_mini_block_id", "adam_mini_write_block_ids",
-           "adam_mini_step", "adam_mini_set_option", "adam_mini_num_buckets",
+           "adam_mini_step", "adam_mini_step_static", "adam_mini_set_option", "adam_mini_num_buckets",
            "adam_mini_profile_enable", "adam_mini_profile_read", "adam_mini_destroy_layout",
            "adam_mini_strerror", "adam_mini_last_hip_error"]
 
@@ -91,6 +92,8 @@ def load(path: Optional[str] = None):
     lib.adam_mini_step.restype = i32
     lib.adam_mini_step.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
                                    ctypes.POINTER(HParams), vp]
+    lib.adam_mini_step_static.restype = i32
+    lib.adam_mini_step_static.argtypes = lib.adam_mini_step.argtypes
     lib.adam_mini_num_buckets.restype = u32
     lib.adam_mini_num_buckets.argtypes = [vp]
     lib.adam_mini_profile_enable.restype = i32
@@ -173,6 +176,12 @@ def adam_mini_step(layout: int, params, grads, exp_avg, v_dev_ptr: int, hp: HPar
                                  ctypes.byref(hp), ctypes.c_void_p(stream)), "adam_mini_step")
 
 
+def adam_mini_step_static(layout: int, params, grads, exp_avg, v_dev_ptr: int, hp: HParams, stream: int = 0) -> None:
+    """Same arguments as adam_mini_step; allocates nothing (fixed scratch inside the library)."""
+    _check(load().adam_mini_step_static(layout, params, grads, exp_avg, ctypes.c_void_p(v_dev_ptr),
+                                        ctypes.byref(hp), ctypes.c_void_p(stream)), "adam_mini_step_static")
+
+
 def adam_mini_num_buckets(layout: int) -> int:
     return int(load().adam_mini_num_buckets(layout))
 
@@ -236,14 +245,17 @@ class AdamMini:
                       pointer_array([t.data_ptr() for t in grads]),
                       pointer_array([t.data_ptr() for t in exp_avg]), v.data_ptr())
 
-    def step(self, lr, beta1, beta2, eps, weight_decay, step: int, stream: Optional[int] = None) -> None:
+    def step(self, lr, beta1, beta2, eps, weight_decay, step: int, stream: Optional[int] = None,
+             static: bool = False) -> None:
+        """static=True calls adam_mini_step_static (no allocation; fixed scratch inside the library)."""
         import torch
         if self._ptrs is None:
             raise RuntimeError("bind() the tensors first")
         if stream is None:
             stream = torch.cuda.current_stream(self.device).cuda_stream
         hp = HParams(lr, beta1, beta2, eps, weight_decay, step)
-        adam_mini_step(self.layout, self._ptrs[0], self._ptrs[1], self._ptrs[2], self._ptrs[3], hp, stream)
+        entry = adam_mini_step_static if static else adam_mini_step
+        entry(self.layout, self._ptrs[0], self._ptrs[1], self._ptrs[2], self._ptrs[3], hp, stream)
 
     def block_ids(self, tensor: int):
         import torch

@@ -14,6 +14,11 @@
 #include "am_kernels.h"
 #include "am_layout.h"
 
+// Work tables, partial sums and step scales of adam_mini_step_static: one array per GPU, part of the
+// library's code object, so that entry point never allocates.  Every GPU the library runs on holds its
+// own copy from the moment the code object is loaded until the process ends.
+static __device__ __align__(256) unsigned char scratch[ADAM_MINI_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_hip_error;
@@ -79,12 +84,14 @@ struct AmPointerCache {
 struct adam_mini_layout {
   AmHostLayout host;
   int device = -1;
+  uint64_t uid = 0;                // never reused, unlike the handle's address
   size_t lds_per_cu = 160 * 1024;  // read from the device by the first call that launches
   bool lds_per_cu_known = false;
   // device state, created by the first call that needs it
   bool device_ready = false;
   AmDeviceMem mem;                 // the layout's own allocations
   AmPointerCache cache;            // pointer lists held by mem.segs
+  AmPointerCache static_cache;     // pointer lists this layout last wrote into the static scratch
   // optional per-bucket timing: events[(step * n_buckets + bucket) * 2 + {0,1}]
   std::vector<hipEvent_t> events;
   uint32_t profile_capacity = 0;   // steps the pool can hold
@@ -466,7 +473,7 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
 // ---------------------------------------------------------------------------
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Byte layout of the work tables inside one allocation.
+// Byte layout of the work tables inside one allocation (or inside the static scratch).
 struct AmTableBytes {
   size_t segs = 0, keys = 0, partials = 0, scales = 0, total = 0;  // offsets, then the size
 };
@@ -579,6 +586,20 @@ int write_pointers(adam_mini_layout* L, void* const* params, const void* const* 
   return ADAM_MINI_OK;
 }
 
+// A byte image into device memory as kernel arguments, kWordsPerLaunch 16-byte words per launch.
+int write_image(unsigned char* dst, const std::vector<unsigned char>& img, hipStream_t stream) {
+  AmWords payload;
+  const size_t words = img.size() / 16;  // images are padded to 256 bytes
+  for (size_t w0 = 0; w0 < words; w0 += kWordsPerLaunch) {
+    const size_t n = words - w0 < (size_t)kWordsPerLaunch ? words - w0 : (size_t)kWordsPerLaunch;
+    std::memcpy(payload.w, img.data() + w0 * 16, n * 16);
+    hipLaunchKernelGGL(am_write_words, dim3(1), dim3(256), 0, stream, reinterpret_cast<am_u32x4*>(dst) + w0,
+                       (uint32_t)n, payload);
+  }
+  AM_HIP(hipGetLastError());
+  return ADAM_MINI_OK;
+}
+
 bool finite_f(float x) { return std::isfinite(x); }
 
 // Everything adam_mini_step checks before it touches a device.
@@ -632,6 +653,29 @@ int launch_step(adam_mini_layout* layout, const AmDeviceMem& mem, float* v_dev, 
   }
   if (timed) layout->profile_used++;
   AM_HIP(hipGetLastError());
+  return ADAM_MINI_OK;
+}
+
+// ---------------------------------------------------------------------------
+// static scratch of adam_mini_step_static: one array per GPU, in the library's code object
+// ---------------------------------------------------------------------------
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU (each holds its own copy)
+uint64_t g_scratch_owner[kMaxDevices];       // uid of the layout whose tables the GPU's array holds (0: none)
+uint64_t g_next_uid = 1;
+
+// Device address of this GPU's copy of the array.  In host code the array's NAME is only a handle for
+// this lookup, never an address a kernel could use.  The device must be current.
+int scratch_address(int device, unsigned char** out) {
+  if (device < 0 || device >= kMaxDevices) return ADAM_MINI_INVALID_ARG;
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    AM_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return ADAM_MINI_HIP_ERROR;
+    g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+  }
+  *out = g_scratch_ptr[device];
   return ADAM_MINI_OK;
 }
 
@@ -699,7 +743,7 @@ int adam_mini_init_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors
   try {
     rc = am_build_layout(descs, n_tensors, grad_dtype, tuning, &L->host);
     if (rc == ADAM_MINI_OK) {
-      for (AmPointerCache* c : {&L->cache}) {
+      for (AmPointerCache* c : {&L->cache, &L->static_cache}) {
         c->p.assign(n_tensors, nullptr);
         c->g.assign(n_tensors, nullptr);
         c->m.assign(n_tensors, nullptr);
@@ -713,6 +757,10 @@ int adam_mini_init_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors
     return rc;
   }
   L->device = device;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    L->uid = g_next_uid++;
+  }
   *out = L;
   return ADAM_MINI_OK;
 }
@@ -781,6 +829,47 @@ int adam_mini_step(adam_mini_layout* layout, void* const* params, const void* co
     layout->cache.keep(params, grads, exp_avg, n);
   }
   return launch_step(layout, layout->mem, v_dev, hp, stream);
+}
+
+int adam_mini_step_static(adam_mini_layout* layout, void* const* params, const void* const* grads,
+                          void* const* exp_avg, float* v_dev, const adam_mini_hparams* hp, void* hip_stream) {
+  int rc = validate_step(layout, params, grads, exp_avg, v_dev, hp);
+  if (rc != ADAM_MINI_OK) return rc;
+  const AmTableBytes b = table_bytes(layout->host);
+  if (b.total > (size_t)ADAM_MINI_STATIC_SCRATCH_BYTES) return ADAM_MINI_TOO_LARGE;
+  if (layout->device >= kMaxDevices) return ADAM_MINI_INVALID_ARG;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  DeviceGuard guard;
+  rc = guard.enter(layout->device);
+  if (rc != ADAM_MINI_OK) return rc;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  unsigned char* base = nullptr;
+  rc = scratch_address(layout->device, &base);  // first call on this GPU: looks the array's device address up
+  if (rc != ADAM_MINI_OK) return rc;
+  if (layout->lds_per_cu_known == false) {
+    rc = query_device(layout);
+    if (rc != ADAM_MINI_OK) return rc;
+    layout->lds_per_cu_known = true;
+  }
+  const AmDeviceMem mem = carve(base, b);
+  const size_t n = layout->host.tensors.size();
+  // The array is shared by every layout stepped this way on the GPU and keeps what the last call left:
+  // unless that call was this layout's, with these pointers, the tables are written again (as kernel
+  // arguments, in stream order).  Partial sums and step scales need no clearing: every one a step reads
+  // was written earlier in the same step.
+  if (g_scratch_owner[layout->device] != layout->uid || !layout->static_cache.same(params, grads, exp_avg, n)) {
+    g_scratch_owner[layout->device] = 0;
+    layout->static_cache.valid = false;
+    try {
+      rc = write_image(base, table_image(layout, b, params, grads, exp_avg), stream);
+    } catch (const std::bad_alloc&) {
+      rc = ADAM_MINI_OUT_OF_MEMORY;
+    }
+    if (rc != ADAM_MINI_OK) return rc;
+    layout->static_cache.keep(params, grads, exp_avg, n);
+    g_scratch_owner[layout->device] = layout->uid;
+  }
+  return launch_step(layout, mem, v_dev, hp, stream);
 }
 
 uint32_t adam_mini_num_buckets(const adam_mini_layout* layout) {
@@ -897,6 +986,7 @@ const char* adam_mini_strerror(int status) {
     case ADAM_MINI_OUT_OF_MEMORY: return "out of memory";
     case ADAM_MINI_HIP_ERROR: return "HIP runtime error";
     case ADAM_MINI_NO_DEVICE: return "layout was built without a device";
+    case ADAM_MINI_TOO_LARGE: return "layout needs more work memory than the static scratch holds";
     default: return "unknown status";
   }
 }

@@ -56,6 +56,14 @@ constexpr int kCapSlackBytes = 1024;
 // table writers: small host tables travel to the device as kernel ARGUMENTS, so an update of the
 // work tables is an ordinary launch on the step's stream: no staging buffer, no copy, no wait.
 // ===========================================================================
+constexpr int kWordsPerLaunch = 224;  // 16-byte words per am_write_words launch (3584 of the 4096 argument bytes)
+struct AmWords {
+  am_u32x4 w[kWordsPerLaunch];
+};
+__global__ __launch_bounds__(256) void am_write_words(am_u32x4* __restrict__ dst, uint32_t n, AmWords payload) {
+  if (threadIdx.x < n) dst[threadIdx.x] = payload.w[threadIdx.x];
+}
+
 constexpr int kPointersPerLaunch = 144;  // segments per am_write_pointers launch (24 bytes each)
 struct AmPointerTriple {
   float* p;

@@ -262,3 +262,19 @@ def test_reducer_flags_are_validated():
         with pytest.raises(B.AdamMiniError):
             B.adam_mini_init_layout([(4096, 4096, 1.0, bad)], B.GRAD_F32, -1)
 
+
+def test_static_step_refuses_layouts_beyond_its_scratch_without_touching_a_device():
+    """adam_mini_step_static checks the layout's need against ADAM_MINI_STATIC_SCRATCH_BYTES on the host."""
+    # column blocks of a [4096, 2^21] matrix: 64 tiles of rows x 2^21 columns of partial sums = 512 MB
+    h = B.adam_mini_init_layout([(4096 * (1 << 21), 4096, 1.0, B.FLAG_STRIDED)], B.GRAD_BF16, 0)
+    lib = B.load()
+    P = B.pointer_array([0x1000])
+    hp = B.HParams(1e-3, 0.9, 0.95, 1e-8, 0.1, 1)
+    assert lib.adam_mini_step_static(h, P, P, P, ctypes.c_void_p(0x1000), ctypes.byref(hp), None) == B.TOO_LARGE
+    assert lib.adam_mini_step_static(h, P, P, P, ctypes.c_void_p(0x1004), ctypes.byref(hp), None) == B.MISALIGNED
+    assert lib.adam_mini_step_static(h, None, P, P, ctypes.c_void_p(0x1000), ctypes.byref(hp), None) == B.INVALID_ARG
+    B.adam_mini_destroy_layout(h)
+    h = B.adam_mini_init_layout([(16, 4, 1.0)], B.GRAD_F32, -1)
+    assert lib.adam_mini_step_static(h, P, P, P, ctypes.c_void_p(0x1000), ctypes.byref(hp), None) == B.NO_DEVICE
+    B.adam_mini_destroy_layout(h)
+    assert "scratch" in B.adam_mini_strerror(B.TOO_LARGE)
