@@ -62,7 +62,8 @@ enum {
   ADAM_MINI_PATH_ROW = 1,         /* whole block held in registers of <= one workgroup; single pass */
   ADAM_MINI_PATH_LARGE = 2,       /* block spans several workgroups: partial sums, finalize, update */
   ADAM_MINI_PATH_ROW_LDS = 3,     /* whole block staged in one workgroup's LDS; single pass */
-  ADAM_MINI_PATH_STRIDED = 4      /* blocks are columns of the stored matrix: column partial sums, finalize, update */
+  ADAM_MINI_PATH_STRIDED = 4,     /* blocks are columns of the stored matrix: column partial sums, finalize, update */
+  ADAM_MINI_PATH_FUSED = 5        /* small tensor list: every tensor in one launch of a generic single-pass kernel */
 };
 
 /* adam_mini_tensor_desc.flags */
@@ -272,6 +273,12 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *   "row_max_units"      blocks above this leave the single-pass register kernel
  *   "lds_max_bytes"      > 0: such blocks whose gradient fits in this much LDS use the LDS-staged kernel
  *   "large_chunk_upt"    units per thread of a chunk in the multi-workgroup path (1, 2, 4, 8, 16)
+ *   "large_slice_mb"     > 0: the multi-workgroup bucket is cut at block boundaries into slices of at most this
+ *                        many MB of gradient, each running its three kernels back to back (a measurement knob:
+ *                        every extra launch costs about 4 us and the second gradient read is not served on
+ *                        chip, so the default 0, one slice, is fastest)
+ *   "large_keep_g"       1: the multi-workgroup kernels read the gradient with ordinary cached loads instead of
+ *                        streaming ones (a measurement knob; no effect seen)
  *   "ew_upt"             units per thread of a tile in the AdamW-equivalent kernel (1, 2, 4, 8)
  *   "grid_cap"           > 0: cap on workgroups per launch (grid-stride loop beyond it)
  *   "row_inflight_kb"    row kernel: resident workgroups per compute unit are capped so that the loads
@@ -281,6 +288,12 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *   "row_blocked"        1: each wavefront of a row team owns a contiguous span of the block
  *   "stream_wg_per_cu"   the same cap for the AdamW-equivalent and large-block update kernels
  *   "strided_wg_per_cu"  the same cap for the column-block (ADAM_MINI_FLAG_STRIDED) update kernel
+ *   "fuse_max_params"    > 0: a tensor list of at most this many elements, all of whose blocks fit one
+ *                        1024-lane team of the generic kernel, is stepped in ONE launch (a step of a small
+ *                        model is bound by the number of launches); 0 = always one launch per kernel variant
+ *   "fuse_target_items"  the one-launch kernel groups blocks so that the list makes about this many work items
+ *                        (default 224, fewer than the chip has compute units, so that every workgroup is
+ *                        resident at once)
  *   "strided_rows"       column-block kernels: rows of the stored matrix per work item (multiple of 4, >= 4)
  *   "xcd_count"          number of XCDs workgroups are dealt to round-robin (power of two; 8 on an
  *                        unpartitioned device, the default)

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libadam_mini.so")
 OK, INVALID_ARG, MISALIGNED, OUT_OF_MEMORY, HIP_ERROR, NO_DEVICE, TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
 STATIC_SCRATCH_BYTES = 16 << 20
 GRAD_F32, GRAD_BF16 = 0, 1
-PATH_ELEMENTWISE, PATH_ROW, PATH_LARGE, PATH_ROW_LDS, PATH_STRIDED = 0, 1, 2, 3, 4
+PATH_ELEMENTWISE, PATH_ROW, PATH_LARGE, PATH_ROW_LDS, PATH_STRIDED, PATH_FUSED = 0, 1, 2, 3, 4, 5
 FLAG_STRIDED = 1
 # adam_mini_tensor_desc.flags bits 4-6: block statistic of g*g that feeds v
 REDUCE_FLAGS = {"mean": 0 << 4, "norm1": 1 << 4, "norm2": 2 << 4, "max": 3 << 4, "min": 4 << 4}

@@ -59,7 +59,8 @@ struct DeviceGuard {
 // Device memory a step works in besides the caller's tensors.
 struct AmDeviceMem {
   AmSeg* segs = nullptr;       // all buckets' segments, concatenated
-  uint32_t* keys = nullptr;    // [2 * n_segs]: item_first of every segment, then lblock_first
+  uint32_t* keys = nullptr;    // [3 * n_segs]: item_first of every segment, then lblock_first, then the item_first
+                               // of the second work-item numbering (column-block update pass)
   float* partials = nullptr;   // LARGE: one float per chunk; STRIDED: [row chunks][columns] per tensor
   float* scales = nullptr;     // LARGE: one step scale per large block; STRIDED: one per column
 };
@@ -256,8 +257,16 @@ constexpr bool am_strided_ok() {
   return CPL == 1 || (sizeof(G) == 2 && VEC == 4);
 }
 
+// A table whose item keys are the bucket's second numbering (the column-block update pass's tiles).
+AmTable second_numbering(const AmTable& tab, const uint32_t* keys_base, uint64_t n_segs_total, const AmBucket& bk) {
+  AmTable t2 = tab;
+  t2.item_keys = keys_base + 2 * n_segs_total + bk.table_offset;
+  return t2;
+}
+
 template <typename G, int VEC, int CPL>
-int launch_strided_cpl(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+int launch_strided_cpl(const AmBucket& bk, const AmTable& tab, const AmTable& tab2, float* v, const AmScalars& sc,
+                       const AmCtx& cx) {
   if constexpr (!am_strided_ok<G, VEC, CPL>()) {
     return ADAM_MINI_INVALID_ARG;
   } else {
@@ -270,57 +279,91 @@ int launch_strided_cpl(const AmBucket& bk, const AmTable& tab, float* v, const A
                        n_items, rows, cx.mem.partials);
     hipLaunchKernelGGL(am_strided_finalize, dim3(fgrid), dim3(256), 0, cx.stream, AM_TAB, n_cols, rows,
                        (const float*)cx.mem.partials, v, cx.mem.scales, sc);
-    return launch_capped(am_strided_update<G, VEC, CPL>, grid, kStridedThreads, cx.t.strided_wg_per_cu, cx, AM_TAB,
-                         n_items, rows, (const float*)cx.mem.scales, sc);
+    const uint32_t n_items2 = (uint32_t)bk.n_items2;
+    return launch_capped(am_strided_update<G, VEC>, grid_for(bk.n_items2, cx.t), kStridedThreads,
+                         cx.t.strided_wg_per_cu, cx, tab2.segs, tab2.item_keys, tab2.lblock_keys, tab2.n_segs,
+                         tab2.xcd_code, n_items2, (const float*)cx.mem.scales, sc);
   }
 }
 
 template <typename G, int VEC>
-int launch_strided(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+int launch_strided(const AmBucket& bk, const AmTable& tab, const AmTable& tab2, float* v, const AmScalars& sc,
+                   const AmCtx& cx) {
   if (bk.var.upt <= 0) return ADAM_MINI_INVALID_ARG;
-  if (bk.var.aux == 2) return launch_strided_cpl<G, VEC, 2>(bk, tab, v, sc, cx);
-  return launch_strided_cpl<G, VEC, 1>(bk, tab, v, sc, cx);
+  if (bk.var.aux == 2) return launch_strided_cpl<G, VEC, 2>(bk, tab, tab2, v, sc, cx);
+  return launch_strided_cpl<G, VEC, 1>(bk, tab, tab2, v, sc, cx);
 }
 
 template <int VEC>
-int launch_strided_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmCtx& cx) {
-  const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t rows = (uint32_t)bk.var.upt;
-  const uint32_t grid = grid_for(bk.n_items, cx.t);
-  if (bk.var.upt <= 0) return ADAM_MINI_INVALID_ARG;
-  if (bk.var.aux == 2)
-    hipLaunchKernelGGL((am_strided_ids<VEC, 2>), dim3(grid), dim3(kStridedThreads), 0, cx.stream, AM_TAB, n_items,
-                       rows, tensor, ids);
-  else
-    hipLaunchKernelGGL((am_strided_ids<VEC, 1>), dim3(grid), dim3(kStridedThreads), 0, cx.stream, AM_TAB, n_items,
-                       rows, tensor, ids);
+int launch_strided_ids(const AmBucket& bk, const AmTable& tab2, uint32_t tensor, uint64_t* ids, const AmCtx& cx) {
+  const uint32_t n_items2 = (uint32_t)bk.n_items2;
+  hipLaunchKernelGGL((am_strided_ids<VEC>), dim3(grid_for(bk.n_items2, cx.t)), dim3(kStridedThreads), 0, cx.stream,
+                     tab2.segs, tab2.item_keys, tab2.lblock_keys, tab2.n_segs, tab2.xcd_code, n_items2, tensor, ids);
   return ADAM_MINI_OK;
+}
+
+// One contiguous run of a LARGE bucket's work items and blocks.
+struct AmSlice {
+  uint32_t item_first, n_items, lblock_first, n_lblocks;
+};
+
+// The bucket as one slice, or -- large_slice_mb > 0 -- cut at block boundaries into slices whose gradients
+// are at most that many MB each: partial sums, finalize and update of a slice then run back to back, so the
+// update's second read of the slice's gradient can be served by the memory-side cache instead of HBM.
+std::vector<AmSlice> large_slices(const AmBucket& bk, size_t grad_bytes, const AmTuning& t) {
+  std::vector<AmSlice> out;
+  if (t.large_slice_mb <= 0) {
+    out.push_back(AmSlice{0u, (uint32_t)bk.n_items, 0u, (uint32_t)bk.n_lblocks});
+    return out;
+  }
+  const uint64_t limit = (uint64_t)t.large_slice_mb << 20;
+  AmSlice cur{0u, 0u, 0u, 0u};
+  uint64_t bytes = 0;
+  for (const AmSeg& s : bk.segs) {
+    const uint64_t block_bytes = s.block_numel * grad_bytes;
+    const uint64_t n_blocks = s.row_len;  // LARGE: the tensor's block count
+    for (uint64_t b = 0; b < n_blocks; ++b) {
+      if (cur.n_lblocks > 0 && bytes + block_bytes > limit) {
+        out.push_back(cur);
+        cur = AmSlice{cur.item_first + cur.n_items, 0u, cur.lblock_first + cur.n_lblocks, 0u};
+        bytes = 0;
+      }
+      cur.n_items += s.chunks_per_block;
+      cur.n_lblocks += 1;
+      bytes += block_bytes;
+    }
+  }
+  if (cur.n_lblocks > 0) out.push_back(cur);
+  return out;
 }
 
 template <typename G, int VEC>
 int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
   const AmVariant& var = bk.var;
-  const uint32_t n_items = (uint32_t)bk.n_items;
-  const uint32_t n_lblocks = (uint32_t)bk.n_lblocks;
-  const uint32_t grid = grid_for(bk.n_items, cx.t);
-  const uint32_t fgrid = grid_for((bk.n_lblocks + 3) / 4, cx.t);
-  const uint32_t pgrid = grid_for((bk.n_items + 3) / 4, cx.t);
   float* partials = cx.mem.partials;
   float* scales = cx.mem.scales;
-#define X(L, U)                                                                                          \
-  if constexpr (VEC * U <= 64) { /* larger chunks are never chosen: they would not fit the registers */  \
-    if (var.lanes == L && var.upt == U) {                                                                \
-      if (bk.alt_reducer)                                                                                \
-        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, true>), dim3(pgrid), dim3(256), 0, cx.stream, \
-                           AM_TAB, n_items, partials);                                                   \
-      else                                                                                               \
-        hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, false>), dim3(pgrid), dim3(256), 0,           \
-                           cx.stream, AM_TAB, n_items, partials);                                        \
-      hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, cx.stream, AM_TAB, n_lblocks,     \
-                         (const float*)partials, v, scales, sc);                                         \
-      return launch_capped(am_large_update<G, VEC, L, U>, grid, L, cx.t.stream_wg_per_cu, cx, AM_TAB,    \
-                           n_items, (const float*)scales, sc);                                           \
-    }                                                                                                    \
+  const uint32_t keep_g = cx.t.large_keep_g != 0;  // ordinary cached gradient loads instead of streaming ones
+#define X(L, U)                                                                                           \
+  if constexpr (VEC * U <= 64) { /* larger chunks are never chosen: they would not fit the registers */   \
+    if (var.lanes == L && var.upt == U) {                                                                 \
+      for (const AmSlice& sl : large_slices(bk, sizeof(G), cx.t)) {                                       \
+        const uint32_t grid = grid_for(sl.n_items, cx.t);                                                 \
+        const uint32_t fgrid = grid_for((sl.n_lblocks + 3) / 4, cx.t);                                    \
+        const uint32_t pgrid = grid_for((sl.n_items + 3) / 4, cx.t);                                      \
+        if (bk.alt_reducer)                                                                               \
+          hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, true>), dim3(pgrid), dim3(256), 0,           \
+                             cx.stream, AM_TAB, sl.item_first, sl.n_items, keep_g, partials);             \
+        else                                                                                              \
+          hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, false>), dim3(pgrid), dim3(256), 0,          \
+                             cx.stream, AM_TAB, sl.item_first, sl.n_items, keep_g, partials);             \
+        hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, cx.stream, AM_TAB,               \
+                           sl.lblock_first, sl.n_lblocks, (const float*)partials, v, scales, sc);         \
+        const int rc = launch_capped(am_large_update<G, VEC, L, U>, grid, L, cx.t.stream_wg_per_cu, cx,   \
+                                     AM_TAB, sl.item_first, sl.n_items, keep_g, (const float*)scales, sc); \
+        if (rc != ADAM_MINI_OK) return rc;                                                                \
+      }                                                                                                   \
+      return ADAM_MINI_OK;                                                                                \
+    }                                                                                                     \
   }
   AM_LARGE_VARIANTS(X)
 #undef X
@@ -374,6 +417,30 @@ int launch_elementwise_ids(const AmBucket& bk, const AmTable& tab, uint32_t tens
   return ADAM_MINI_INVALID_ARG;
 }
 
+template <typename G, int VEC>
+int launch_fused(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+  if constexpr (VEC != 4) {
+    return ADAM_MINI_INVALID_ARG;  // the layout builder fuses lists of whole 4-element units only
+  } else {
+    const uint32_t n_items = (uint32_t)bk.n_items;
+    hipLaunchKernelGGL((am_fused_kernel<G, VEC>), dim3(grid_for(bk.n_items, cx.t)), dim3(kFusedThreads), 0, cx.stream,
+                       AM_TAB, n_items, v, sc);
+    return ADAM_MINI_OK;
+  }
+}
+
+template <int VEC>
+int launch_fused_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint64_t* ids, const AmCtx& cx) {
+  if constexpr (VEC != 4) {
+    return ADAM_MINI_INVALID_ARG;
+  } else {
+    const uint32_t n_items = (uint32_t)bk.n_items;
+    hipLaunchKernelGGL((am_fused_ids<VEC>), dim3(grid_for(bk.n_items, cx.t)), dim3(kFusedThreads), 0, cx.stream,
+                       AM_TAB, n_items, tensor, ids);
+    return ADAM_MINI_OK;
+  }
+}
+
 // Dispatch on (gradient type, vec) -> template arguments.
 template <typename G_, int VEC_>
 struct AmTag {
@@ -420,7 +487,7 @@ AmTable bucket_table(const adam_mini_layout* L, const AmDeviceMem& mem, const Am
                         : fam == AM_FAM_STRIDED                      ? t.xcd_chunk_strided
                                                                      : t.xcd_chunk_stream;
   tab.xcd_code = 32;  // identity
-  if (chunk > 0 && t.xcd_count > 1) tab.xcd_code = floor_log2(chunk) | (floor_log2(t.xcd_count) << 8);
+  if (chunk > 0 && t.xcd_count > 1 && fam != AM_FAM_FUSED) tab.xcd_code = floor_log2(chunk) | (floor_log2(t.xcd_count) << 8);
   return tab;
 }
 
@@ -435,11 +502,14 @@ int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, 
       case AM_FAM_ROW_LDS:
         return launch_row_lds<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       case AM_FAM_STRIDED:
-        return launch_strided<typename T::G, T::VEC>(bk, tab, v, sc, cx);
+        return launch_strided<typename T::G, T::VEC>(bk, tab, second_numbering(tab, cx.mem.keys, L->host.n_segs, bk), v,
+                                                     sc, cx);
       case AM_FAM_LARGE:
         return launch_large<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       case AM_FAM_ELEMENTWISE:
         return launch_elementwise<typename T::G, T::VEC>(bk, tab, v, sc, cx);
+      case AM_FAM_FUSED:
+        return launch_fused<typename T::G, T::VEC>(bk, tab, v, sc, cx);
       default:
         return (int)ADAM_MINI_INVALID_ARG;
     }
@@ -457,11 +527,13 @@ int launch_bucket_ids(const adam_mini_layout* L, const AmBucket& bk, uint32_t te
       case AM_FAM_ROW_LDS:
         return launch_row_lds_ids<VEC>(bk, tab, tensor, ids, cx);
       case AM_FAM_STRIDED:
-        return launch_strided_ids<VEC>(bk, tab, tensor, ids, cx);
+        return launch_strided_ids<VEC>(bk, second_numbering(tab, cx.mem.keys, L->host.n_segs, bk), tensor, ids, cx);
       case AM_FAM_LARGE:
         return launch_large_ids<VEC>(bk, tab, tensor, ids, cx);
       case AM_FAM_ELEMENTWISE:
         return launch_elementwise_ids<VEC>(bk, tab, tensor, ids, cx);
+      case AM_FAM_FUSED:
+        return launch_fused_ids<VEC>(bk, tab, tensor, ids, cx);
       default:
         return (int)ADAM_MINI_INVALID_ARG;
     }
@@ -482,7 +554,7 @@ AmTableBytes table_bytes(const AmHostLayout& h) {
   AmTableBytes b;
   b.segs = 0;
   b.keys = round_up(h.n_segs * sizeof(AmSeg), 256);
-  b.partials = b.keys + round_up(2 * h.n_segs * sizeof(uint32_t), 256);
+  b.partials = b.keys + round_up(3 * h.n_segs * sizeof(uint32_t), 256);
   b.scales = b.partials + round_up(h.n_partials * sizeof(float), 256);
   b.total = b.scales + round_up(h.n_lblocks * sizeof(float), 256);
   return b;
@@ -516,6 +588,7 @@ std::vector<unsigned char> table_image(const adam_mini_layout* L, const AmTableB
       segs[bk.table_offset + i] = s;
       keys[bk.table_offset + i] = s.item_first;
       keys[n + bk.table_offset + i] = s.lblock_first;
+      keys[2 * n + bk.table_offset + i] = i < bk.item2_first.size() ? bk.item2_first[i] : 0u;
     }
   return img;
 }
@@ -710,6 +783,10 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "row_blocked") g_tuning.row_blocked = value;
   else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
   else if (k == "strided_wg_per_cu") g_tuning.strided_wg_per_cu = value;
+  else if (k == "fuse_max_params") g_tuning.fuse_max_params = value;
+  else if (k == "fuse_target_items") { if (value < 1) return ADAM_MINI_INVALID_ARG; g_tuning.fuse_target_items = value; }
+  else if (k == "large_slice_mb") g_tuning.large_slice_mb = value;
+  else if (k == "large_keep_g") g_tuning.large_keep_g = value;
   else if (k == "strided_rows") {
     if (value < 4 || value > 65536 || value % 4 != 0) return ADAM_MINI_INVALID_ARG;
     g_tuning.strided_rows = value;
@@ -934,7 +1011,11 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
     o.lanes = bk.var.lanes;
     o.upt = bk.var.upt;
     o.n_tensors = (uint32_t)bk.segs.size();
-    o.n_kernels = (bk.var.family == AM_FAM_LARGE || bk.var.family == AM_FAM_STRIDED) ? 3u : 1u;
+    o.n_kernels = bk.var.family == AM_FAM_STRIDED ? 3u : 1u;
+    if (bk.var.family == AM_FAM_LARGE) {
+      const size_t grad_bytes = layout->host.grad_dtype == ADAM_MINI_GRAD_BF16 ? 2 : 4;
+      o.n_kernels = 3u * (uint32_t)large_slices(bk, grad_bytes, layout->host.tuning).size();
+    }
     o.n_items = bk.n_items;
     for (const AmSeg& s : bk.segs) {
       const AmTensorInfo& ti = layout->host.tensors[s.tensor];
@@ -948,8 +1029,11 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
     const char* kname = bk.var.family == AM_FAM_ROW ? "am_row_kernel"
                         : bk.var.family == AM_FAM_LARGE ? "am_large_update"
                         : bk.var.family == AM_FAM_ROW_LDS ? "am_row_lds_kernel" : "am_elementwise";
-    if (bk.var.family == AM_FAM_STRIDED)
-      std::snprintf(o.kernel, sizeof o.kernel, "am_strided_update<%s, %d, %d>", gname, bk.var.vec, bk.var.aux);
+    if (bk.var.family == AM_FAM_FUSED)
+      std::snprintf(o.kernel, sizeof o.kernel, "am_fused_kernel<%s, %d>", gname, bk.var.vec);
+    else if (bk.var.family == AM_FAM_STRIDED)
+      std::snprintf(o.kernel, sizeof o.kernel, "am_strided_update<%s, %d> after am_strided_partial<%s, %d, %d>", gname,
+                    bk.var.vec, gname, bk.var.vec, bk.var.aux);
     else if (bk.var.family == AM_FAM_ROW_LDS)
       std::snprintf(o.kernel, sizeof o.kernel, "%s<%s, %d>", kname, gname, bk.var.vec);
     else

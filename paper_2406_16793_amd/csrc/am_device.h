@@ -109,6 +109,17 @@ __device__ __forceinline__ typename AmRaw<G, VEC>::T am_load_grad_raw(const void
 #endif
 }
 
+// The same load with the cache policy chosen at run time (uniform over the launch): `keep` asks for an
+// ordinary cached load, so that a second pass over the same bytes soon after may find them on chip.
+template <typename G, int VEC>
+__device__ __forceinline__ typename AmRaw<G, VEC>::T am_load_grad_raw_policy(const void* __restrict__ base, uint64_t e,
+                                                                            bool keep) {
+  using T = typename AmRaw<G, VEC>::T;
+  const AM_GLOBAL T* src = am_global(reinterpret_cast<const T*>(reinterpret_cast<const G*>(base) + e));
+  if (keep) return *src;
+  return __builtin_nontemporal_load(src);
+}
+
 __device__ __forceinline__ void am_widen(float r, float (&out)[1]) { out[0] = r; }
 __device__ __forceinline__ void am_widen(am_f32x4 r, float (&out)[4]) {
   out[0] = r.x; out[1] = r.y; out[2] = r.z; out[3] = r.w;
@@ -133,6 +144,12 @@ __device__ __forceinline__ void am_widen(am_u32x4 r, float (&out)[8]) {
 template <typename G, int VEC>
 __device__ __forceinline__ void am_load_grad(const void* __restrict__ base, uint64_t e, float (&out)[VEC]) {
   am_widen(am_load_grad_raw<G, VEC>(base, e), out);
+}
+
+template <typename G, int VEC>
+__device__ __forceinline__ void am_load_grad_policy(const void* __restrict__ base, uint64_t e, bool keep,
+                                                    float (&out)[VEC]) {
+  am_widen(am_load_grad_raw_policy<G, VEC>(base, e, keep), out);
 }
 
 // ---------------------------------------------------------------------------

@@ -263,6 +263,189 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_KERNEL_PAR
 }
 
 // ===========================================================================
+// FUSED family: the whole tensor list of a SMALL layout in one launch.  A step of a small model is
+// bound by the number of launches, not by bandwidth, so instead of one launch per kernel variant
+// every tensor goes through this one generic kernel: 1024-thread workgroups, each working on one
+// item of one tensor.
+//   row items   a group of up to 1024 / T whole blocks, each held in the registers of a team of T lanes
+//               (T = 16, 64, 256 or 1024: the smallest that holds the block at kFusedUpt units per lane),
+//               exactly the single-pass scheme of am_row_kernel
+//   tile items  1024 * kFusedUpt units of a tensor whose blocks have one element (AdamW-equivalent)
+// T and the number of blocks per item are properties of the tensor (AmSeg::chunks_per_block = T |
+// blocks per item << 16; 0 marks a tile tensor), so they are uniform over a workgroup and the barrier
+// below is too.  The host picks the blocks per item so that a small list makes no more items than the
+// chip has compute units: a launch whose workgroups are all resident at once costs little more than an
+// empty one (about 6 us back to back), a second round of workgroups nearly doubles it; teams beyond the
+// item's blocks simply idle.
+// ===========================================================================
+
+template <typename G, int VEC>
+__global__ __launch_bounds__(kFusedThreads) void am_fused_kernel(AM_KERNEL_PARAMS, uint32_t n_items,
+                                                                 float* __restrict__ v, AmScalars sc) {
+  constexpr int WAVES = kFusedThreads / 64;
+  __shared__ float xch[WAVES];     // wavefront results
+  __shared__ float xch_v[WAVES];   // a team's old v, left by the team's first wavefront
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    // a later item of a grid-stride pass reuses the exchange slots: everyone must be done reading them
+    // (items differ in whether they use the slots at all, so alternating two sets would not be enough)
+    if (grp != blockIdx.x) __syncthreads();
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
+    const uint32_t s = am_find_seg(item_keys, n_segs, item);
+    const AmSeg& S = segs[s];
+    const uint32_t local = item - item_keys[s];
+    const uint32_t T = S.chunks_per_block & 0xffffu, per_item = S.chunks_per_block >> 16;
+    const float decay = sc.lr_wd * S.wd_scale;
+    float gv[kFusedUpt][VEC], mv[kFusedUpt][VEC], pv[kFusedUpt][VEC];
+
+    if (T == 0) {
+      // tile of a one-element-block tensor: dense v, every statistic of the 1-vector g*g is g*g
+      float* __restrict__ vt = v + S.v_first;
+      float vv[kFusedUpt][VEC];
+      const uint64_t unit0 = (uint64_t)local * (kFusedThreads * kFusedUpt);
+#pragma unroll
+      for (int k = 0; k < kFusedUpt; ++k) {
+        const uint64_t u = unit0 + threadIdx.x + (uint64_t)k * kFusedThreads;
+        if (u < S.units_per_block) {
+          const uint64_t e = u * VEC;
+          am_load_grad<G, VEC>(S.g, e, gv[k]);
+          am_load_f32<VEC>(S.m, e, mv[k]);
+          am_load_f32<VEC>(S.p, e, pv[k]);
+          am_load_f32<VEC>(vt, e, vv[k]);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < kFusedUpt; ++k) {
+        const uint64_t u = unit0 + threadIdx.x + (uint64_t)k * kFusedThreads;
+        if (u < S.units_per_block) {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) {
+            float v_new, scale;
+            am_block_scalars(gv[k][j] * gv[k][j], vv[k][j], sc, &v_new, &scale);
+            vv[k][j] = v_new;
+            am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale, decay, sc);
+          }
+          const uint64_t e = u * VEC;
+          am_store_f32<VEC>(S.m, e, mv[k]);
+          am_store_f32<VEC>(S.p, e, pv[k]);
+          am_store_f32<VEC>(vt, e, vv[k]);
+        }
+      }
+      continue;   // uniform over the workgroup: T belongs to the item
+    }
+
+    // row item: team `threadIdx.x / T` takes block local * per_item + team, if the item has that many
+    const uint32_t team = threadIdx.x / T, lane = threadIdx.x % T;
+    const uint64_t block = (uint64_t)local * per_item + team;
+    const bool active = team < per_item && block < S.row_len;   // row_len holds the tensor's block count here
+    const uint64_t units = S.units_per_block;
+    const uint64_t elem0 = block * S.block_numel;
+    const uint64_t v_idx = S.v_first + block;
+    float v_old = 0.0f;
+    if (T <= 64) {
+      // a team inside one wavefront: every lane reads the same scalar (one broadcast request); the store
+      // below comes later in the same wavefront's program order
+      if (active) v_old = v[v_idx];
+    } else if (active && lane == 0) {
+      v_old = v[v_idx];   // one lane per team touches v: its later store cannot race a read
+    }
+#pragma unroll
+    for (int k = 0; k < kFusedUpt; ++k) {
+      const uint64_t u = lane + (uint64_t)k * T;
+      if (active && u < units) {
+        const uint64_t e = elem0 + u * VEC;
+        am_load_grad<G, VEC>(S.g, e, gv[k]);
+        am_load_f32<VEC>(S.m, e, mv[k]);
+        am_load_f32<VEC>(S.p, e, pv[k]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) gv[k][j] = 0.0f;
+      }
+    }
+    const uint32_t red = S.reducer;
+    float ss;
+    if (am_red_is_sum_sq(red)) {
+      ss = 0.0f;
+#pragma unroll
+      for (int k = 0; k < kFusedUpt; ++k)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) ss = fmaf(gv[k][j], gv[k][j], ss);
+      ss = T == 16 ? am_row16_sum(ss) : am_wave_sum(ss);
+    } else {
+      ss = am_red_identity(red);
+#pragma unroll
+      for (int k = 0; k < kFusedUpt; ++k)
+        if (active && lane + (uint64_t)k * T < units) ss = am_red_accumulate(red, gv[k], ss);
+      ss = T == 16 ? am_row16_reduce(red, ss) : am_wave_reduce(red, ss);
+    }
+    // T > 64: a team is TW whole wavefronts; the first lane of the team's first wavefront holds v_old
+    const uint32_t wave = threadIdx.x >> 6, TW = T >> 6, wave0 = team * TW;
+    if (TW > 1) {
+      float* slot = xch;
+      float* slot_v = xch_v;
+      if ((threadIdx.x & 63) == 0) slot[wave] = ss;
+      if (lane == 0) slot_v[wave] = v_old;
+      __syncthreads();
+      ss = slot[wave0];
+      if (am_red_is_sum_sq(red)) {
+        for (uint32_t w = 1; w < TW; ++w) ss += slot[wave0 + w];
+      } else {
+        for (uint32_t w = 1; w < TW; ++w) ss = am_combine(red, ss, slot[wave0 + w]);
+      }
+      v_old = slot_v[wave0];
+    }
+    float v_new, scale;
+    am_block_scalars(am_red_finish(red, ss, (float)S.block_numel), v_old, sc, &v_new, &scale);
+    if (active && lane == 0) v[v_idx] = v_new;
+#pragma unroll
+    for (int k = 0; k < kFusedUpt; ++k) {
+      const uint64_t u = lane + (uint64_t)k * T;
+      if (active && u < units) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale, decay, sc);
+        const uint64_t e = elem0 + u * VEC;
+        am_store_f32<VEC>(S.m, e, mv[k]);
+        am_store_f32<VEC>(S.p, e, pv[k]);
+      }
+    }
+  }
+}
+
+// Same walk, writing the v index of every element of tensor `tensor`.
+template <int VEC>
+__global__ __launch_bounds__(kFusedThreads) void am_fused_ids(AM_KERNEL_PARAMS, uint32_t n_items, uint32_t tensor,
+                                                              uint64_t* __restrict__ ids) {
+  for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
+    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
+    const uint32_t s = am_find_seg(item_keys, n_segs, item);
+    const AmSeg& S = segs[s];
+    if (S.tensor != tensor) continue;
+    const uint32_t local = item - item_keys[s];
+    const uint32_t T = S.chunks_per_block & 0xffffu, per_item = S.chunks_per_block >> 16;
+    if (T == 0) {
+      const uint64_t unit0 = (uint64_t)local * (kFusedThreads * kFusedUpt);
+#pragma unroll
+      for (int k = 0; k < kFusedUpt; ++k) {
+        const uint64_t u = unit0 + threadIdx.x + (uint64_t)k * kFusedThreads;
+        if (u < S.units_per_block)
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) ids[u * VEC + j] = S.v_first + u * VEC + j;
+      }
+      continue;
+    }
+    const uint32_t team = threadIdx.x / T, lane = threadIdx.x % T;
+    const uint64_t block = (uint64_t)local * per_item + team;
+    if (team >= per_item || block >= S.row_len) continue;
+#pragma unroll
+    for (int k = 0; k < kFusedUpt; ++k) {
+      const uint64_t u = lane + (uint64_t)k * T;
+      if (u < S.units_per_block)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) ids[block * S.block_numel + u * VEC + j] = S.v_first + block;
+    }
+  }
+}
+
+// ===========================================================================
 // ROW_LDS family: one block per 1024-thread workgroup, too big for the registers of the team
 // but small enough that its gradient fits the compute unit's 160 KB of LDS.  Pass 1 streams g
 // from HBM into LDS (as it sits in memory) while summing squares; pass 2 streams m and p,
@@ -431,8 +614,10 @@ __device__ __forceinline__ uint64_t am_chunk_unit(uint64_t unit0, int k) {
 // parameter because that path needs the chunk's gradient a second time from the registers, which
 // would otherwise cost the plain sum of squares its occupancy (67 -> 120 VGPRs).
 template <typename G, int VEC, int THREADS, int UPT, bool ALT>
-__global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
-                                                        uint32_t n_items, float* __restrict__ partials) {
+__global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS, uint32_t item_base,
+                                                        uint32_t n_items, uint32_t keep_g,
+                                                        float* __restrict__ partials) {
+  // work items [item_base, item_base + n_items) of the bucket: the whole bucket, or one slice of it
   constexpr int STEPS = THREADS * UPT / 64;  // units per lane
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint32_t n_groups = (n_items + 3) / 4;
@@ -441,7 +626,7 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
     uint32_t item = first + wave;
     const bool active = item < n_items;
     if (!active) item = n_items - 1;
-    item = __builtin_amdgcn_readfirstlane(item);
+    item = __builtin_amdgcn_readfirstlane(item_base + item);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     if constexpr (sizeof(G) == 2 && VEC == 4 && STEPS % 2 == 0) {
@@ -454,7 +639,7 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
         for (int k = 0; k < STEPS / 2; ++k) {
           const uint64_t u = it.unit0 + 2 * ((uint64_t)k * 64 + lane);
           if (active && u < S.units_per_block) {
-            am_load_grad<G, 8>(S.g, it.elem0 + u * VEC, g8[k]);
+            am_load_grad_policy<G, 8>(S.g, it.elem0 + u * VEC, keep_g != 0, g8[k]);
           } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) g8[k][j] = 0.0f;
@@ -475,7 +660,7 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
     for (int k = 0; k < STEPS; ++k) {
       const uint64_t u = it.unit0 + (uint64_t)k * 64 + lane;
       if (active && u < S.units_per_block) {
-        am_load_grad<G, VEC>(S.g, it.elem0 + u * VEC, gv[k]);
+        am_load_grad_policy<G, VEC>(S.g, it.elem0 + u * VEC, keep_g != 0, gv[k]);
       } else {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) gv[k][j] = 0.0f;
@@ -505,13 +690,15 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS,
 
 // One wavefront per large block: sums the block's chunk partials in a fixed order
 // (lane-strided, then butterfly) in double, updates v and stores the step scale.
-__global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS,
+__global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS, uint32_t lblock_base,
                                                          uint32_t n_lblocks, const float* __restrict__ partials,
                                                          float* __restrict__ v, float* __restrict__ scales,
                                                          AmScalars sc) {
+  // large blocks [lblock_base, lblock_base + n_lblocks) of the bucket
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t waves_per_grid = gridDim.x * 4;
-  for (uint32_t lb = blockIdx.x * 4 + (threadIdx.x >> 6); lb < n_lblocks; lb += waves_per_grid) {
+  for (uint32_t i = blockIdx.x * 4 + (threadIdx.x >> 6); i < n_lblocks; i += waves_per_grid) {
+    const uint32_t lb = lblock_base + i;
     const uint32_t s = am_find_seg(lblock_keys, n_segs, lb);
     const AmSeg& S = segs[s];
     const uint32_t block = lb - lblock_keys[s];
@@ -536,11 +723,11 @@ __global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS,
 }
 
 template <typename G, int VEC, int THREADS, int UPT>
-__global__ __launch_bounds__(THREADS) void am_large_update(AM_KERNEL_PARAMS,
-                                                           uint32_t n_items, const float* __restrict__ scales,
-                                                           AmScalars sc) {
+__global__ __launch_bounds__(THREADS) void am_large_update(AM_KERNEL_PARAMS, uint32_t item_base,
+                                                           uint32_t n_items, uint32_t keep_g,
+                                                           const float* __restrict__ scales, AmScalars sc) {
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
-    const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
+    const uint32_t item = item_base + am_xcd_swizzle(grp, n_items, xcd_code);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
     const AmSeg& S = *it.seg;
     const float scale = scales[it.lblock];
@@ -551,7 +738,7 @@ __global__ __launch_bounds__(THREADS) void am_large_update(AM_KERNEL_PARAMS,
       const uint64_t u = am_chunk_unit<THREADS>(it.unit0, k);
       if (u < S.units_per_block) {
         const uint64_t e = it.elem0 + u * VEC;
-        am_load_grad<G, VEC>(S.g, e, gv[k]);
+        am_load_grad_policy<G, VEC>(S.g, e, keep_g != 0, gv[k]);
         am_load_f32<VEC>(S.m, e, mv[k]);
         am_load_f32<VEC>(S.p, e, pv[k]);
       }
@@ -599,14 +786,13 @@ __global__ __launch_bounds__(THREADS) void am_large_ids(AM_KERNEL_PARAMS,
 // row, and column sums need no cross-lane reduction at all: a lane only ever adds up its own columns.
 //   am_strided_partial   per tile: the statistic of g^2 of each column over the tile's rows
 //   am_strided_finalize  per column: fixed-order combination over the row chunks (double), v update, step scale
-//   am_strided_update    per tile: m and p update with the per-column step scales
+//   am_strided_update    m and p update with the per-column step scales (linear walk, see below)
 // CPL = 2 (bf16 gradients in 4-element units, rows of an even number of units): the partial pass gives a
 // lane two ADJACENT units, so its 8 bf16 values are one 128-bit load (a read-only pass needs 128-bit
-// loads to keep up); the update pass gives a lane units `lane` and `lane + 256` of the group, so its
-// 128-bit accesses to m and p stay lane-contiguous.  Both passes index the partial sums and the step
-// scales by column, so the two unit maps never have to agree.
+// loads to keep up).  Both passes index the partial sums and the step scales by column, so their unit
+// maps never have to agree.
 // ===========================================================================
-constexpr int kStridedLoads = 4;  // units in flight per thread in either pass
+constexpr int kStridedLoads = 8;  // rows in flight per thread in the partial pass
 
 struct AmStridedItem {
   const AmSeg* seg;
@@ -713,86 +899,84 @@ __global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uin
   }
 }
 
-template <typename G, int VEC, int CPL>
+// The update pass walks the stored matrix LINEARLY: a work item is a tile of 256 * kStridedUpdateUpt
+// consecutive units of the tensor (whole rows one after the other, as am_large_update walks a block), so
+// a workgroup's accesses are one contiguous run per array; the column of a unit, and with it the step
+// scale, follows from the unit's position inside its row.  (Tiles shaped like the partial pass's -- a
+// column group over many rows -- touch 8 KB pieces 128 KB apart and ran 20 % slower.)  The pass has work
+// items of its own: `item_keys` here is the bucket's SECOND key array.
+template <typename G, int VEC>
 __global__ __launch_bounds__(kStridedThreads) void am_strided_update(AM_KERNEL_PARAMS, uint32_t n_items,
-                                                                     uint32_t rows_per_item,
                                                                      const float* __restrict__ scales,
                                                                      AmScalars sc) {
-  constexpr int ROWS = kStridedLoads / CPL;    // rows in flight (CPL units each)
+  constexpr int UPT = kStridedUpdateUpt;
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
     const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
-    const AmStridedItem it = am_strided_decode<CPL>(AM_TABLE_ARGS, item, rows_per_item);
-    const AmSeg& S = *it.seg;
-    const uint64_t rows = S.block_numel, row_len = S.row_len;
+    const uint32_t s = am_find_seg(item_keys, n_segs, item);
+    const AmSeg& S = segs[s];
+    const uint64_t units_per_row = S.units_per_block;
+    const uint64_t total_units = S.block_numel * units_per_row;   // rows * units per row
+    const uint64_t unit0 = (uint64_t)(item - item_keys[s]) * (kStridedThreads * UPT);
     const float decay = sc.lr_wd * S.wd_scale;
-    const uint32_t n_rows = (uint32_t)(rows - it.row0 < rows_per_item ? rows - it.row0 : rows_per_item);
-    uint64_t unit[CPL];
-    bool on[CPL];
-    float scale[CPL][VEC];
+    const float* __restrict__ tensor_scales = scales + S.lblock_first;
+    float gv[UPT][VEC], mv[UPT][VEC], pv[UPT][VEC], scale[UPT][VEC];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      unit[c] = it.unit0 + threadIdx.x + (uint64_t)c * kStridedThreads;
-      on[c] = unit[c] < S.units_per_block;
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = unit0 + threadIdx.x + (uint64_t)k * kStridedThreads;
+      if (u < total_units) {
+        const uint64_t e = u * VEC;
+        am_load_grad<G, VEC>(S.g, e, gv[k]);
+        am_load_f32<VEC>(S.m, e, mv[k]);
+        am_load_f32<VEC>(S.p, e, pv[k]);
+        const uint64_t col = (u % units_per_row) * VEC;            // a unit never straddles rows
+        if constexpr (VEC % 4 == 0) {
+          // the bucket's scale array is 256-byte aligned and every tensor of the bucket has a multiple of
+          // VEC columns, so a unit's scales are whole 16-byte words (cached loads: they are re-read by every row)
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) scale[c][j] = 0.0f;
-      if (on[c]) {
-        const float* src = scales + S.lblock_first + unit[c] * VEC;
+          for (int q = 0; q < VEC / 4; ++q) {
+            const am_f32x4 w = *am_global(reinterpret_cast<const am_f32x4*>(tensor_scales + col) + q);
+            scale[k][4 * q + 0] = w.x; scale[k][4 * q + 1] = w.y; scale[k][4 * q + 2] = w.z; scale[k][4 * q + 3] = w.w;
+          }
+        } else {
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) scale[c][j] = src[j];
+          for (int j = 0; j < VEC; ++j) scale[k][j] = tensor_scales[col + j];
+        }
       }
     }
-    for (uint32_t r = 0; r < n_rows; r += ROWS) {
-      float gv[ROWS][CPL][VEC], mv[ROWS][CPL][VEC], pv[ROWS][CPL][VEC];
 #pragma unroll
-      for (int q = 0; q < ROWS; ++q) {
-        const uint64_t row = it.row0 + r + q;
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = unit0 + threadIdx.x + (uint64_t)k * kStridedThreads;
+      if (u < total_units) {
 #pragma unroll
-        for (int c = 0; c < CPL; ++c)
-          if (on[c] && r + q < n_rows) {
-            const uint64_t e = row * row_len + unit[c] * VEC;
-            am_load_grad<G, VEC>(S.g, e, gv[q][c]);
-            am_load_f32<VEC>(S.m, e, mv[q][c]);
-            am_load_f32<VEC>(S.p, e, pv[q][c]);
-          }
-      }
-#pragma unroll
-      for (int q = 0; q < ROWS; ++q) {
-        const uint64_t row = it.row0 + r + q;
-#pragma unroll
-        for (int c = 0; c < CPL; ++c)
-          if (on[c] && r + q < n_rows) {
-#pragma unroll
-            for (int j = 0; j < VEC; ++j)
-              am_update_elem(gv[q][c][j], mv[q][c][j], pv[q][c][j], scale[c][j], decay, sc);
-            const uint64_t e = row * row_len + unit[c] * VEC;
-            am_store_f32<VEC>(S.m, e, mv[q][c]);
-            am_store_f32<VEC>(S.p, e, pv[q][c]);
-          }
+        for (int j = 0; j < VEC; ++j) am_update_elem(gv[k][j], mv[k][j], pv[k][j], scale[k][j], decay, sc);
+        const uint64_t e = u * VEC;
+        am_store_f32<VEC>(S.m, e, mv[k]);
+        am_store_f32<VEC>(S.p, e, pv[k]);
       }
     }
   }
 }
 
-template <int VEC, int CPL>
+// The update pass's walk, writing the v index of every element of tensor `tensor`.
+template <int VEC>
 __global__ __launch_bounds__(kStridedThreads) void am_strided_ids(AM_KERNEL_PARAMS, uint32_t n_items,
-                                                                  uint32_t rows_per_item, uint32_t tensor,
-                                                                  uint64_t* __restrict__ ids) {
+                                                                  uint32_t tensor, uint64_t* __restrict__ ids) {
+  constexpr int UPT = kStridedUpdateUpt;
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
     const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
-    const AmStridedItem it = am_strided_decode<CPL>(AM_TABLE_ARGS, item, rows_per_item);
-    const AmSeg& S = *it.seg;
+    const uint32_t s = am_find_seg(item_keys, n_segs, item);
+    const AmSeg& S = segs[s];
     if (S.tensor != tensor) continue;
+    const uint64_t units_per_row = S.units_per_block;
+    const uint64_t total_units = S.block_numel * units_per_row;
+    const uint64_t unit0 = (uint64_t)(item - item_keys[s]) * (kStridedThreads * UPT);
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      const uint64_t unit = it.unit0 + threadIdx.x + (uint64_t)c * kStridedThreads;   // the update pass's unit map
-      if (unit >= S.units_per_block) continue;
-      for (uint32_t r = 0; r < rows_per_item; ++r) {
-        const uint64_t row = it.row0 + r;
-        if (row < S.block_numel) {
-          const uint64_t e = row * S.row_len + unit * VEC;
+    for (int k = 0; k < UPT; ++k) {
+      const uint64_t u = unit0 + threadIdx.x + (uint64_t)k * kStridedThreads;
+      if (u < total_units) {
+        const uint64_t col = (u % units_per_row) * VEC;
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) ids[e + j] = S.v_first + unit * VEC + j;
-        }
+        for (int j = 0; j < VEC; ++j) ids[u * VEC + j] = S.v_first + col + j;
       }
     }
   }

@@ -58,6 +58,7 @@ int am_path_kind(const AmVariant& v) {
     case AM_FAM_ROW: return ADAM_MINI_PATH_ROW;
     case AM_FAM_ROW_LDS: return ADAM_MINI_PATH_ROW_LDS;
     case AM_FAM_STRIDED: return ADAM_MINI_PATH_STRIDED;
+    case AM_FAM_FUSED: return ADAM_MINI_PATH_FUSED;
     default: return ADAM_MINI_PATH_LARGE;
   }
 }
@@ -112,6 +113,35 @@ AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel
   return var;
 }
 
+// A small list goes through the one-launch generic kernel when every tensor fits it -- contiguous blocks of
+// whole 4-element units that one 1024-lane team can hold, or one-element blocks in whole units with a
+// 16-byte aligned v slice -- and when that saves launches, i.e. the tuned kernels would need more than one.
+// (Descriptors are validated by the caller's loop; invalid ones just answer no.)
+bool am_list_is_fusable(int grad_dtype, const adam_mini_tensor_desc* descs, uint32_t n_tensors, const AmTuning& t) {
+  if (t.fuse_max_params <= 0) return false;
+  uint64_t total = 0, v_next = 0;
+  AmVariant first{};
+  bool several = false;
+  for (uint32_t k = 0; k < n_tensors; ++k) {
+    const adam_mini_tensor_desc& d = descs[k];
+    if (d.numel == 0 || d.block_numel == 0 || d.numel % d.block_numel != 0) return false;
+    total += d.numel;
+    if (total > (uint64_t)t.fuse_max_params) return false;
+    const uint64_t n_blocks = d.numel / d.block_numel;
+    if ((d.flags & ADAM_MINI_FLAG_STRIDED) != 0 && n_blocks > 1 && d.block_numel > 1) return false;
+    if (d.block_numel == 1) {
+      if (d.numel % 4 != 0 || v_next % 4 != 0) return false;
+    } else if (d.block_numel % 4 != 0 || d.block_numel / 4 > (uint64_t)kFusedThreads * kFusedUpt) {
+      return false;
+    }
+    const AmVariant var = am_choose_variant(grad_dtype, d.numel, d.block_numel, v_next, t);
+    if (k == 0) first = var;
+    else if (!same_variant(first, var)) several = true;
+    v_next += n_blocks;
+  }
+  return several;
+}
+
 int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int grad_dtype,
                     const AmTuning& tuning, AmHostLayout* out) {
   if (!descs || !out || n_tensors == 0) return ADAM_MINI_INVALID_ARG;
@@ -120,6 +150,15 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
   out->tuning = tuning;
   out->tensors.clear();
   out->buckets.clear();
+  const bool fused = am_list_is_fusable(grad_dtype, descs, n_tensors, tuning);
+  uint64_t fused_item_bytes = 0;
+  if (fused) {
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < n_tensors; ++k) total += descs[k].numel;
+    const uint64_t target_items = tuning.fuse_target_items > 0 ? (uint64_t)tuning.fuse_target_items : 1;
+    fused_item_bytes = total * (16 + (grad_dtype == ADAM_MINI_GRAD_BF16 ? 2u : 4u)) / target_items;
+    if (fused_item_bytes < 32 * 1024) fused_item_bytes = 32 * 1024;
+  }
   uint64_t v_next = 0;
   for (uint32_t k = 0; k < n_tensors; ++k) {
     const adam_mini_tensor_desc& d = descs[k];
@@ -140,7 +179,12 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     // (contiguous) tensor and with one row every element is its own block: both are plain layouts.
     ti.strided = (d.flags & ADAM_MINI_FLAG_STRIDED) != 0 && ti.n_blocks > 1 && d.block_numel > 1;
     AmVariant var{};
-    if (ti.strided) {
+    if (fused) {
+      var.family = AM_FAM_FUSED;
+      var.vec = 4;
+      var.lanes = kFusedThreads;
+      var.upt = kFusedUpt;
+    } else if (ti.strided) {
       const int native = grad_dtype == ADAM_MINI_GRAD_BF16 ? (tuning.bf16_vec == 8 ? 8 : 4) : 4;
       var.family = AM_FAM_STRIDED;
       // a row must be a whole number of units (the per-column step scales are read one float at a time,
@@ -179,7 +223,27 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     s.reducer = (d.flags & ADAM_MINI_REDUCE_MASK) >> 4;  // same numbering as the kernels' AM_RED_*
     if ((d.flags & ADAM_MINI_REDUCE_MASK) > ADAM_MINI_REDUCE_NORM1) bk.alt_reducer = true;
     uint64_t items = 0;
-    if (var.family == AM_FAM_ELEMENTWISE) {
+    if (var.family == AM_FAM_FUSED) {
+      if (d.block_numel == 1) {
+        s.block_numel = d.numel;
+        s.units_per_block = d.numel / 4;
+        s.chunks_per_block = 0;
+        items = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
+      } else {
+        s.units_per_block = d.block_numel / 4;
+        uint32_t team = 16;
+        while ((uint64_t)team * kFusedUpt < s.units_per_block) team *= 4;   // 16, 64, 256, 1024
+        // blocks per item: enough bytes per workgroup that the whole list makes about fuse_target_items items
+        const uint64_t block_bytes = d.block_numel * (16 + (grad_dtype == ADAM_MINI_GRAD_BF16 ? 2u : 4u));
+        uint64_t per_item = (fused_item_bytes + block_bytes - 1) / block_bytes;
+        const uint64_t cap = (uint64_t)kFusedThreads / team;
+        if (per_item > cap) per_item = cap;
+        if (per_item < 1) per_item = 1;
+        s.chunks_per_block = team | ((uint32_t)per_item << 16);
+        s.row_len = ti.n_blocks;
+        items = (ti.n_blocks + per_item - 1) / per_item;
+      }
+    } else if (var.family == AM_FAM_ELEMENTWISE) {
       s.block_numel = d.numel;
       s.units_per_block = (d.numel + (uint64_t)var.vec - 1) / (uint64_t)var.vec;
       items = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
@@ -196,6 +260,11 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       bk.n_partials += row_chunks * cols;
       bk.n_lblocks += cols;                                                // one step scale per column
       items = row_chunks * groups;
+      // the update pass walks the tensor linearly in tiles of its own
+      const uint64_t tile = (uint64_t)kStridedThreads * kStridedUpdateUpt;
+      bk.item2_first.push_back((uint32_t)bk.n_items2);
+      bk.n_items2 += (rows * s.units_per_block + tile - 1) / tile;
+      if (bk.n_items2 >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
     } else if (var.family == AM_FAM_ROW || var.family == AM_FAM_ROW_LDS) {
       s.units_per_block = d.block_numel / (uint64_t)var.vec;
       items = ti.n_blocks;
@@ -204,6 +273,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       const uint64_t cpb = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
       if (cpb >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
       s.chunks_per_block = (uint32_t)cpb;
+      s.row_len = ti.n_blocks;
       items = ti.n_blocks * cpb;
       bk.n_lblocks += ti.n_blocks;
     }

@@ -26,6 +26,8 @@ struct AmBucket {
   AmVariant var;
   std::vector<AmSeg> segs;  // pointers left null here; filled at step time
   uint64_t n_items = 0;     // total work items (ROW: blocks, LARGE: chunks, ELEMENTWISE: tiles)
+  std::vector<uint32_t> item2_first;  // STRIDED: per segment, work items of the UPDATE pass before this tensor
+  uint64_t n_items2 = 0;    // STRIDED: work items of the update pass (linear tiles)
   uint64_t n_lblocks = 0;   // LARGE: total blocks, STRIDED: total columns (length of the scale scratch)
   uint64_t n_partials = 0;  // STRIDED: floats of partial sums the bucket needs
   uint64_t table_offset = 0;  // index of segs[0] in the concatenated device table
@@ -47,20 +49,28 @@ struct AmTuning {
                                     //      in this many bytes of LDS use the LDS-staged single-pass kernel
   int64_t large_chunk_upt = 4;      // LARGE: units per thread of a 256-thread chunk (1, 2, 4, 8 or 16)
   int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (1, 2, 4 or 8)
+  int64_t large_slice_mb = 0;       // LARGE: > 0 cuts the bucket into slices of at most this many MB of gradient,
+                                    //   each running partial sums, finalize and update back to back; 0 = one slice
+  int64_t large_keep_g = 0;         // LARGE: 1 = the gradient is read with ordinary cached loads in both passes
   int64_t grid_cap = 0;             // > 0: at most this many workgroups per launch (grid-stride beyond)
   int64_t row_inflight_kb = 80;     // row kernel: resident workgroups per compute unit are capped so that the
                                     //   loads they keep in flight stay near this many KB (0 = no cap)
   int64_t row_wg_per_cu = 0;        // > 0: fixed cap on resident row-kernel workgroups per compute unit (overrides row_inflight_kb)
   int64_t row_blocked = 0;          // 1: each wavefront of a row team owns a contiguous span of the block
-  int64_t strided_wg_per_cu = 4;    // > 0: cap on resident workgroups per compute unit of the column-block update kernel
+  int64_t strided_wg_per_cu = 2;    // > 0: cap on resident workgroups per compute unit of the column-block update kernel
   int64_t stream_wg_per_cu = 2;     // > 0: same for the elementwise / large-update streaming kernels
-  int64_t strided_rows = 64;        // column-block kernels: rows of the stored matrix per work item (multiple of 4)
+  int64_t fuse_max_params = 16 << 20;  // > 0: a tensor list of at most this many elements whose blocks all fit one
+                                    //   team of the generic kernel is stepped in ONE launch (small models are
+                                    //   bound by the number of launches); 0 = never
+  int64_t fuse_target_items = 224;  // the one-launch kernel: blocks are grouped so that the list makes about this many
+                                    //   work items (fewer than the chip has compute units: one round of workgroups)
+  int64_t strided_rows = 128;       // column-block kernels: rows of the stored matrix per work item (multiple of 4)
   int64_t xcd_count = 8;            // XCDs the hardware deals workgroups to round-robin (power of two; 8 when the
                                     //   device is one partition)
   int64_t xcd_chunk = 64;           // row kernels: consecutive workgroup passes one XCD walks (power of two; 0 = the
                                     //   hardware's round-robin order, item by item)
   int64_t xcd_chunk_stream = 16;    // same for the elementwise and large-block kernels
-  int64_t xcd_chunk_strided = 0;    // same for the column-block kernels
+  int64_t xcd_chunk_strided = 16;   // same for the column-block kernels
 };
 
 struct AmHostLayout {
@@ -77,6 +87,10 @@ struct AmHostLayout {
 // Returns ADAM_MINI_OK or ADAM_MINI_INVALID_ARG.
 int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int grad_dtype,
                     const AmTuning& tuning, AmHostLayout* out);
+
+// Does the whole list qualify for the one-launch generic kernel (AM_FAM_FUSED)?
+bool am_list_is_fusable(int grad_dtype, const adam_mini_tensor_desc* descs, uint32_t n_tensors,
+                        const AmTuning& tuning);
 
 // Kernel variant that serves a tensor.
 AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel, uint64_t v_first,

@@ -15,7 +15,8 @@ enum AmFamily : int {
   AM_FAM_ROW = 1,          // item = one block, held in the registers of a team of LANES threads
   AM_FAM_LARGE = 2,        // item = one chunk of a block; partial sums + finalize + update
   AM_FAM_ROW_LDS = 3,      // item = one block, gradient staged in the workgroup's LDS
-  AM_FAM_STRIDED = 4       // blocks are columns: item = (row chunk, group of 256 or 512 column units)
+  AM_FAM_STRIDED = 4,      // blocks are columns: item = (row chunk, group of 256 or 512 column units)
+  AM_FAM_FUSED = 5         // small layouts: every tensor in one launch; item = a workgroup's worth of blocks or units
 };
 
 // One tensor inside one bucket.  Device pointers are filled in at step time.
@@ -28,12 +29,12 @@ struct AmSeg {
   uint64_t units_per_block;  // block_numel / VEC (ELEMENTWISE: ceil(numel / VEC))
   uint32_t item_first;    // number of work items of the bucket before this tensor
   uint32_t lblock_first;  // LARGE: number of large blocks of the bucket before this tensor
-  uint32_t chunks_per_block; // LARGE: work items per block; otherwise 1
+  uint32_t chunks_per_block; // LARGE: work items per block; FUSED: lanes of the team that holds a block | blocks per work item << 16 (0: one-element blocks); otherwise 1
   uint32_t tensor;        // index in the caller's tensor list
   float wd_scale;         // lambda_k = weight_decay * wd_scale
   uint32_t reducer;       // block statistic of g .* g that feeds v: 0 mean (the method), 1 1-norm, 2 2-norm, 3 max, 4 min
   uint64_t aux;           // STRIDED: index of the tensor's first partial sum in the scratch
-  uint64_t row_len;       // STRIDED: elements per stored row (= number of blocks C)
+  uint64_t row_len;       // STRIDED: elements per stored row (= number of blocks C); LARGE, FUSED: number of blocks
 };
 // STRIDED reuses the fields as: block_numel = rows R of the stored [R, C] matrix (elements per block),
 // units_per_block = units per ROW (C / VEC), chunks_per_block = column groups per row chunk,
@@ -54,6 +55,15 @@ struct AmTable {
 // kStridedThreads lanes owns kStridedThreads * aux units of a row (aux = AmVariant::aux, 1 or 2) over
 // AmVariant::upt consecutive rows.
 constexpr int kStridedThreads = 256;
+// The STRIDED update pass has work items of its own: tiles of kStridedThreads * kStridedUpdateUpt consecutive
+// units of the tensor (AmBucket::item2_first / n_items2, the bucket's second key array on the device).
+constexpr int kStridedUpdateUpt = 4;
+
+// Workgroup of the FUSED family, shared by the layout builder and the kernel: 1024 threads; a block is
+// held by a team of 16, 64, 256 or 1024 of them at up to kFusedUpt units per lane (AmSeg::chunks_per_block
+// holds the team size and, shifted left by 16, the blocks per work item; 0 for a tensor of one-element blocks; AmSeg::row_len holds the number of blocks).
+constexpr int kFusedThreads = 1024;
+constexpr int kFusedUpt = 4;
 
 // Per-step scalars, computed on the host in double and rounded once to fp32.
 struct AmScalars {

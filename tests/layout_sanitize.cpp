@@ -75,7 +75,7 @@ void check_layout(const std::vector<adam_mini_tensor_desc>& descs, int grad_dtyp
     n_segs += bk.segs.size();
     CHECK(!bk.segs.empty(), "%s: empty bucket", what);
     CHECK(var.vec == 1 || var.vec == 4 || (var.vec == 8 && grad_dtype == ADAM_MINI_GRAD_BF16), "%s: vec %d", what, var.vec);
-    uint64_t items = 0, lblocks = 0, partials = 0;
+    uint64_t items = 0, items2 = 0, lblocks = 0, partials = 0;
     for (const AmSeg& s : bk.segs) {
       CHECK(s.tensor < descs.size(), "%s: tensor index in segment", what);
       if (s.tensor >= descs.size()) return;
@@ -148,6 +148,30 @@ void check_layout(const std::vector<adam_mini_tensor_desc>& descs, int grad_dtyp
           partials += row_chunks * cols;
           lblocks += cols;
           seg_items = row_chunks * s.chunks_per_block;
+          // second numbering: linear tiles of the update pass
+          const size_t si = (size_t)(&s - bk.segs.data());
+          CHECK(bk.item2_first.size() == bk.segs.size(), "%s: second numbering has %zu entries", what, bk.item2_first.size());
+          if (si < bk.item2_first.size()) CHECK(bk.item2_first[si] == items2, "%s: item2_first", what);
+          items2 += ceil_div(rows * s.units_per_block, (uint64_t)kStridedThreads * kStridedUpdateUpt);
+          break;
+        }
+        case AM_FAM_FUSED: {
+          CHECK(!ti.strided && var.vec == 4 && var.lanes == kFusedThreads && var.upt == kFusedUpt, "%s: fused variant", what);
+          CHECK(L.buckets.size() == 1, "%s: a fused list has one bucket", what);
+          if (d.block_numel == 1) {
+            CHECK(d.numel % 4 == 0 && ti.v_first % 4 == 0, "%s: fused one-element blocks need whole units and an aligned v slice", what);
+            CHECK(s.chunks_per_block == 0 && s.block_numel == d.numel && s.units_per_block * 4 == d.numel, "%s: fused tile tensor", what);
+            seg_items = ceil_div(s.units_per_block, (uint64_t)kFusedThreads * kFusedUpt);
+          } else {
+            const uint64_t team = s.chunks_per_block & 0xffffu, per_item = s.chunks_per_block >> 16;
+            CHECK(team == 16 || team == 64 || team == 256 || team == 1024, "%s: fused team of %" PRIu64, what, team);
+            CHECK(per_item >= 1 && per_item * team <= (uint64_t)kFusedThreads, "%s: %" PRIu64 " blocks per fused item", what, per_item);
+            CHECK(d.block_numel % 4 == 0 && s.units_per_block * 4 == d.block_numel && s.block_numel == d.block_numel, "%s: fused units", what);
+            CHECK(s.units_per_block <= team * kFusedUpt, "%s: fused block of %" PRIu64 " units in a team of %" PRIu64, what, s.units_per_block, team);
+            CHECK(team == 16 || s.units_per_block > (team / 4) * kFusedUpt, "%s: fused team larger than needed", what);
+            CHECK(s.row_len == ti.n_blocks, "%s: fused block count", what);
+            seg_items = per_item ? ceil_div(ti.n_blocks, per_item) : 0;
+          }
           break;
         }
         default:
@@ -163,10 +187,16 @@ void check_layout(const std::vector<adam_mini_tensor_desc>& descs, int grad_dtyp
     }
     if (var.family == AM_FAM_STRIDED) {
       CHECK(bk.n_lblocks == lblocks && bk.n_partials == partials, "%s: column scratch", what);
+      CHECK(bk.n_items2 == items2 && bk.n_items2 < (1ull << 31), "%s: update-pass items", what);
       CHECK(L.n_partials >= bk.n_partials && L.n_lblocks >= bk.n_lblocks, "%s: scratch of a column bucket", what);
     }
   }
   CHECK(L.n_segs == n_segs && n_segs == descs.size(), "%s: segment total", what);
+  if (!L.buckets.empty() && L.buckets[0].var.family == AM_FAM_FUSED) {
+    uint64_t total = 0;
+    for (const adam_mini_tensor_desc& d : descs) total += d.numel;
+    CHECK(tuning.fuse_max_params > 0 && total <= (uint64_t)tuning.fuse_max_params, "%s: fused list of %" PRIu64 " elements", what, total);
+  }
   for (size_t k = 0; k < descs.size(); ++k) CHECK(seen[k] == 1, "%s: tensor %zu in %d segments", what, k, seen[k]);
 }
 
@@ -201,6 +231,8 @@ AmTuning random_tuning(Rng& r) {
   t.large_chunk_upt = r.pick(chunk_upt);
   t.ew_upt = r.pick(ew_upt);
   t.strided_rows = r.pick(rows);
+  t.fuse_max_params = r.in(0, 3) == 0 ? 0 : (int64_t)r.in(1, 40000000);
+  t.fuse_target_items = (int64_t)r.in(1, 2000);
   return t;
 }
 
@@ -229,6 +261,32 @@ void random_layouts() {
     const int rc = build(descs, trial % 2 ? ADAM_MINI_GRAD_BF16 : ADAM_MINI_GRAD_F32, t, what);
     CHECK(rc == ADAM_MINI_OK, "%s: rc %d", what, rc);
   }
+}
+
+// Small lists of whole 4-element units: the ones the one-launch generic kernel may serve.
+void small_regular_layouts() {
+  Rng r(99);
+  const uint64_t blocks[] = {4, 8, 64, 256, 260, 1024, 1028, 4096, 4100, 11008, 16384, 16388};
+  int fused = 0;
+  for (int trial = 0; trial < 300; ++trial) {
+    std::vector<adam_mini_tensor_desc> descs;
+    const int n = (int)r.in(1, 10);
+    for (int i = 0; i < n; ++i) {
+      if (r.in(0, 5) == 0) descs.push_back(desc(4 * r.in(1, 3000), 1));
+      else descs.push_back(desc(r.in(1, 300), r.pick(blocks), 1.0f, (uint32_t)r.in(0, 4) << 4));
+    }
+    const AmTuning t = trial % 3 == 0 ? AmTuning() : random_tuning(r);
+    AmHostLayout L;
+    char what[64];
+    std::snprintf(what, sizeof what, "small list %d", trial);
+    const int g = trial % 2 ? ADAM_MINI_GRAD_BF16 : ADAM_MINI_GRAD_F32;
+    const int rc = am_build_layout(descs.data(), (uint32_t)descs.size(), g, t, &L);
+    CHECK(rc == ADAM_MINI_OK, "%s: rc %d", what, rc);
+    if (rc != ADAM_MINI_OK) continue;
+    check_layout(descs, g, t, L, what);
+    if (L.buckets[0].var.family == AM_FAM_FUSED) ++fused;
+  }
+  CHECK(fused > 30, "only %d of 300 small lists took the one-launch kernel", fused);
 }
 
 void crafted_layouts() {
@@ -300,6 +358,7 @@ void limits_and_flags() {
 
 int main() {
   random_layouts();
+  small_regular_layouts();
   crafted_layouts();
   limits_and_flags();
   if (g_failures) {

@@ -168,6 +168,12 @@ def test_layout_of_benchmark_configs(oracle, name):
         assert voff[k] == oracle.block_id(numel, bnum, k, 0)
         e = numel[k] - 1
         assert B.adam_mini_block_id(h, k, e) == oracle.block_id(numel, bnum, k, e)
+    if name == "tiny":
+        # a small list that the tuned kernels would serve in three launches: one launch of the generic kernel
+        assert set(kind) == {B.PATH_FUSED}
+        assert len(B.adam_mini_profile_read(h)) == 1
+        B.adam_mini_destroy_layout(h)
+        return
     for s, kd in zip(wl.specs, kind):
         if "query" in s.name or "key" in s.name:
             assert kd in (B.PATH_LARGE, B.PATH_ROW_LDS) or s.block_numel <= 16384 * 2
@@ -278,3 +284,28 @@ def test_static_step_refuses_layouts_beyond_its_scratch_without_touching_a_devic
     assert lib.adam_mini_step_static(h, P, P, P, ctypes.c_void_p(0x1000), ctypes.byref(hp), None) == B.NO_DEVICE
     B.adam_mini_destroy_layout(h)
     assert "scratch" in B.adam_mini_strerror(B.TOO_LARGE)
+
+
+def test_small_lists_take_one_launch_only_when_that_saves_launches():
+    """The generic one-launch kernel serves a list only if it is small, every block fits one team of it,
+    and the tuned kernels would need more than one launch."""
+    def kinds(descs, dtype=B.GRAD_F32):
+        h = B.adam_mini_init_layout(descs, dtype, -1)
+        out = B.adam_mini_export_layout(h)[1]
+        n = len(B.adam_mini_profile_read(h))
+        B.adam_mini_destroy_layout(h)
+        return out, n
+    rows, heads, gains, adamw = (1024 * 256, 256, 1.0), (4 * 16384, 16384, 1.0), (256, 256, 0.0), (4096, 1, 1.0)
+    assert kinds([rows, heads, gains]) == ([B.PATH_FUSED] * 3, 1)
+    assert kinds([adamw, rows, heads]) == ([B.PATH_FUSED] * 3, 1)               # one-element blocks, aligned v slice
+    assert kinds([rows, rows]) == ([B.PATH_ROW] * 2, 1)                          # already one launch
+    assert kinds([rows, (8 * 16388, 16388, 1.0)])[0][0] == B.PATH_ROW            # a block beyond one team
+    assert kinds([rows, (30, 3, 1.0)])[0][0] == B.PATH_ROW                       # not whole 4-element units
+    assert kinds([rows, (64 * 48, 64, 1.0, B.FLAG_STRIDED)])[0][0] == B.PATH_ROW  # column blocks
+    assert kinds([gains, (3, 1, 1.0), adamw])[0][0] == B.PATH_ROW                # one-element blocks, v slice not aligned
+    assert kinds([(1 << 24, 4096, 1.0), heads])[0][0] == B.PATH_ROW              # more than fuse_max_params elements
+    B.adam_mini_set_option("fuse_max_params", 0)
+    try:
+        assert kinds([rows, heads, gains])[1] == 2      # 16-lane teams for the rows and the gains, a 1024-lane team for the heads
+    finally:
+        B.adam_mini_set_option("reset", 0)

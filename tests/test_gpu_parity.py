@@ -80,11 +80,28 @@ def test_block_ids_device_layout_is_bit_exact(oracle):
         run.close()
 
 
-def test_config1_tiny_10_steps():
+@pytest.mark.parametrize("one_launch", [True, False])
+def test_config1_tiny_10_steps(one_launch, oracle):
+    """The tiny configuration through the generic one-launch kernel (the default for a list this small)
+    and through the three launches of the tuned kernels."""
     import gpu_harness as H
-    from paper_2406_16793_amd import workloads
+    import torch
+    from paper_2406_16793_amd import binding as B, workloads
     wl = workloads.get("tiny")
-    run, st, worst = H.run_both(wl, check_every_step=True)
+    try:
+        if not one_launch:
+            B.adam_mini_set_option("fuse_max_params", 0)
+        run, st, worst = H.run_both(wl, check_every_step=True)
+    finally:
+        B.adam_mini_set_option("reset", 0)
+    assert B.adam_mini_num_buckets(run.opt.layout) == (1 if one_launch else 3)
+    assert worst < 1e-5
+    numel = [s.numel for s in wl.specs]
+    bnum = [s.block_numel for s in wl.specs]
+    for k in range(len(wl.specs)):
+        got = run.opt.block_ids(k)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.block_ids_tensor(numel, bnum, k).astype(np.int64)), k
     print("tiny: worst normwise rel err %.3g" % worst, flush=True)
     # the 0/(0+eps) case: row 0 of the embedding never gets a gradient: only decay acts, m = v = 0
     assert float(run.v[0]) == 0.0 and float(run.m[0][:256].abs().max()) == 0.0

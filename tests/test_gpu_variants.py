@@ -12,15 +12,18 @@ import variant_cases as V
 
 pytestmark = pytest.mark.gpu
 
-_PARAMS = [pytest.param(opts, gd, id="%s-%s" % (cid, gd)) for cid, opts, gds in V.CASES for gd in gds]
+_PARAMS = [pytest.param(opts, gd, None, id="%s-%s" % (cid, gd)) for cid, opts, gds in V.CASES for gd in gds]
+_PARAMS += [pytest.param(opts, gd, reds, id="%s-%s" % (cid, gd)) for cid, opts, gds, reds in V.FUSED_CASES for gd in gds]
 
 
-@pytest.mark.parametrize("options,grad_dtype", _PARAMS)
-def test_variant_matches_the_oracle(options, grad_dtype, oracle):
+@pytest.mark.parametrize("options,grad_dtype,fused_reducers", _PARAMS)
+def test_variant_matches_the_oracle(options, grad_dtype, fused_reducers, oracle):
+    """fused_reducers is None: the mixed list of every kernel family; otherwise the small list that the
+    one-launch generic kernel serves (unless the options switch it off), with those block statistics."""
     import gpu_harness as H
     import torch
     from paper_2406_16793_amd import binding as B, workloads
-    specs = V.specs()
+    specs = V.specs() if fused_reducers is None else V.fused_specs(fused_reducers)
     rtol = 5e-3 if grad_dtype == "bf16" else 1e-5
     wl = workloads.Workload("variants", 92, specs, grad_dtype, 3, rtol=rtol, zero_row_prob=0.2,
                             zero_row_tensors=(2, 10))
@@ -29,6 +32,10 @@ def test_variant_matches_the_oracle(options, grad_dtype, oracle):
             B.adam_mini_set_option(k, v)
         run, st, worst = H.run_both(wl, check_every_step=True)
         assert worst < 1e-5, (options, worst)
+        if fused_reducers is not None:
+            kinds = set(B.adam_mini_export_layout(run.opt.layout)[1])
+            want_fused = options.get("fuse_max_params", 1 << 30) >= sum(s.numel for s in specs)
+            assert (kinds == {B.PATH_FUSED}) == want_fused, (options, kinds)
         numel = [s.numel for s in specs]
         bnum = [s.block_numel for s in specs]
         strided = [s.strided for s in specs]

@@ -9,7 +9,7 @@ import variant_cases as V
 from paper_2406_16793_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-FAM_EW, FAM_ROW, FAM_LARGE, FAM_ROW_LDS, FAM_STRIDED = 0, 1, 2, 3, 4
+FAM_EW, FAM_ROW, FAM_LARGE, FAM_ROW_LDS, FAM_STRIDED, FAM_FUSED = 0, 1, 2, 3, 4, 5
 
 
 def _variant_list(src, name):
@@ -32,6 +32,8 @@ def _launchable():
             out |= {(FAM_EW, grad, vec, l, u) for l, u in ew}
             if vec > 1:
                 out.add((FAM_ROW_LDS, grad, vec, 1024, 1))
+            if vec == 4:
+                out.add((FAM_FUSED, grad, vec, 1024, 4))
             out.add((FAM_STRIDED, grad, vec, 256, 1))
             if grad == "bf16" and vec == 4:
                 out.add((FAM_STRIDED, grad, vec, 256, 2))          # two units of a row per lane
@@ -39,11 +41,13 @@ def _launchable():
 
 
 def test_variant_cases_reach_every_kernel_instantiation():
-    specs = V.specs()
-    descs = [(s.numel, s.block_numel, s.wd_scale, B.FLAG_STRIDED if s.strided else 0) for s in specs]
+    def descs_of(specs):
+        return [(s.numel, s.block_numel, s.wd_scale, B.FLAG_STRIDED if s.strided else 0) for s in specs]
+    mixed, small = descs_of(V.specs()), descs_of(V.fused_specs())
     reached = set()
     try:
-        for cid, opts, grads in [("default", {}, V.BOTH)] + V.CASES:
+        for cid, opts, grads, descs in ([("default", {}, V.BOTH, mixed)] + [c + (mixed,) for c in V.CASES]
+                                        + [c[:3] + (small,) for c in V.FUSED_CASES]):
             for grad in grads:
                 B.adam_mini_set_option("reset", 0)
                 for k, v in opts.items():
@@ -69,8 +73,8 @@ def test_every_option_key_is_exercised():
     body = src[src.index("int adam_mini_set_option"):src.index("int adam_mini_init_layout")]
     keys = set(re.findall(r'k == "([a-z0-9_]+)"', body)) - {"reset"}
     used = set()
-    for _, opts, _ in V.CASES:
-        used |= set(opts)
+    for case in V.CASES + V.FUSED_CASES:
+        used |= set(case[1])
     other_tests = "".join(open(os.path.join(ROOT, "tests", f)).read() for f in os.listdir(os.path.join(ROOT, "tests"))
                           if f.startswith("test_gpu") or f.startswith("test_zz"))
     missing = {k for k in keys - used if ('"%s"' % k) not in other_tests}

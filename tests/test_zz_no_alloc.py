@@ -9,6 +9,7 @@ BIG = [(300, 4096), (3, 49152), (2, 200000), (1, 524288), (5000, 1), (70, 64), (
 BIG_COLUMNS = [(1024, 300), (1000, 33), (260, 3)]
 SMALL = [(40, 256), (2, 20001 * 5), (17, 1)]
 SMALL_COLUMNS = [(264, 9)]
+ONE_LAUNCH = [(300, 64), (5, 4096), (3, 16384), (1, 256, 0.0)]      # a list the generic one-launch kernel serves
 HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
 
 
@@ -55,18 +56,23 @@ def test_static_scratch_step_equals_the_allocating_step(grad_dtype, oracle):
     import oracle as orc
     big = _pair(BIG, BIG_COLUMNS, grad_dtype, 1)
     small = _pair(SMALL, SMALL_COLUMNS, grad_dtype, 2)
+    one = _pair(ONE_LAUNCH, [], grad_dtype, 3)
     specs = big[0].specs
     st = orc.OracleState([s.numel for s in specs], [s.block_numel for s in specs], [s.wd_scale for s in specs],
                          [x.cpu().numpy() for x in big[0].p], strided=[s.strided for s in specs])
     for t in range(1, 5):
         _new_grads(big, 10 + t)
         _new_grads(small, 20 + t)
+        _new_grads(one, 30 + t)
         big[0].opt.step(step=t, **HP)
         small[0].opt.step(step=t, **HP)
+        one[0].opt.step(step=t, **HP)
         big[1].opt.step(step=t, static=True, **HP)        # the array now holds the big list's tables and sums
         small[1].opt.step(step=t, static=True, **HP)      # ... and now the smaller list's, over their remains
+        one[1].opt.step(step=t, static=True, **HP)
         _assert_same(big, "big list, step %d" % t)
         _assert_same(small, "small list, step %d" % t)
+        _assert_same(one, "one-launch list, step %d" % t)
         st.step([H.grad_to_host(g) for g in big[1].g], orc.Hyper.from_f32(**HP))
     worst = H.compare(big[1], st, 5e-3 if grad_dtype == "bf16" else 1e-5, label="static")
     assert worst < 1e-5
@@ -84,7 +90,7 @@ def test_static_scratch_step_equals_the_allocating_step(grad_dtype, oracle):
     small[0].opt.step(step=6, **HP)
     small[1].opt.step(step=6, static=True, **HP)
     _assert_same(small, "small list, mixed entry points")
-    for run in big + small:
+    for run in big + small + one:
         run.close()
 
 

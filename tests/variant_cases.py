@@ -26,6 +26,18 @@ def specs():
     return out
 
 
+# A small list of whole 4-element units whose blocks each fit one 1024-lane team: the kind the one-launch
+# generic kernel serves (teams of 64, 256 and 1024 lanes, one-element blocks with an aligned v slice first).
+FUSED_LIST = [(4096 * 3, 1), (300, 64), (1030, 256), (70, 260), (33, 768), (40, 1024), (9, 1028), (5, 4096),
+              (3, 4100), (3, 11008), (5, 16384), (2, 16380), (1, 4096, 0.0), (67, 8), (8 * 513, 1)]
+
+
+def fused_specs(reducers=("mean",)):
+    from paper_2406_16793_amd.partition import TensorSpec
+    return [TensorSpec("f%d" % i, (b[0], b[1]), b[1], b[2] if len(b) > 2 else 1.0, False, reducers[i % len(reducers)])
+            for i, b in enumerate(FUSED_LIST)]
+
+
 def _o(**kw):
     return dict(kw)
 
@@ -55,6 +67,9 @@ CASES = [
     ("large_chunk_upt=2", _o(large_chunk_upt=2), BOTH),
     ("large_chunk_upt=8", _o(large_chunk_upt=8), BOTH),
     ("large_chunk_upt=16", _o(large_chunk_upt=16), BOTH),
+    ("large_slice_mb=1", _o(large_slice_mb=1), BOTH),               # the multi-workgroup bucket in several slices
+    ("large_slice_mb=2-keep", _o(large_slice_mb=2, large_keep_g=1, grid_cap=3, large_chunk_upt=2), BOTH),
+    ("large_keep_g", _o(large_keep_g=1), ("bf16",)),
     ("ew_upt=1", _o(ew_upt=1), BOTH),
     ("ew_upt=2", _o(ew_upt=2), BOTH),
     ("ew_upt=8", _o(ew_upt=8), BOTH),
@@ -99,6 +114,20 @@ CASES = [
     ("xcd_count=16", _o(xcd_count=16, xcd_chunk=1, xcd_chunk_stream=1, xcd_chunk_strided=1), ("f32",)),
     ("xcd_chunks=1", _o(xcd_chunk=1, xcd_chunk_stream=1, xcd_chunk_strided=1), ("bf16",)),
     ("xcd_chunks=0", _o(xcd_chunk=0, xcd_chunk_stream=0, xcd_chunk_strided=0), ("f32",)),
+]
+
+
+# (id, options, gradient types, block statistics) for the small list above
+FUSED_CASES = [
+    ("fused", _o(), BOTH, ("mean",)),
+    ("fused-grid_cap=1", _o(grid_cap=1), BOTH, ("mean",)),
+    ("fused-grid_cap=5", _o(grid_cap=5), BOTH, ("mean", "max", "norm2", "min", "norm1")),
+    ("fused-statistics", _o(), BOTH, ("max", "norm2", "mean", "min", "norm1")),
+    ("fused-one-block-per-item", _o(fuse_target_items=100000), BOTH, ("mean", "max")),
+    ("fused-full-items", _o(fuse_target_items=1), BOTH, ("norm2", "mean")),
+    ("fused-16-items-grid_cap=2", _o(fuse_target_items=16, grid_cap=2), ("bf16",), ("mean", "min")),
+    ("fused-off", _o(fuse_max_params=0), BOTH, ("mean",)),
+    ("fused-limit-below-the-list", _o(fuse_max_params=100000), ("bf16",), ("mean",)),
 ]
 
 
