@@ -196,6 +196,26 @@ int adam_mini_step(adam_mini_layout* layout, void* const* params,
                    const adam_mini_hparams* hp, void* hip_stream);
 
 /*
+ * The same step with the hyper-parameters in DEVICE memory, for training loops that run under a HIP
+ * graph: adam_mini_step bakes lr, the betas and above all the step counter t into its kernel
+ * arguments, so a captured step replays as the SAME step; here a one-thread kernel enqueued ahead of
+ * the step's own reads *hp_dev, forms the step's scalars from it (in double, as the host does) and the
+ * step kernels read those from device memory.
+ *   hp_dev   device pointer (8-byte aligned) to one adam_mini_hparams; read -- and with
+ *            ADAM_MINI_STEP_ADVANCE written -- when the work runs on the stream, not during the call
+ *   flags    0, or ADAM_MINI_STEP_ADVANCE: hp_dev->step is incremented first and the new value is
+ *            this step's t (start it at 0).  A graph that captured such a call therefore performs
+ *            steps t+1, t+2, ... on successive replays; change lr by writing hp_dev->lr between replays.
+ * The values in *hp_dev cannot be validated by the host: the caller keeps them in the ranges
+ * adam_mini_step accepts (t >= 1 when used, betas in [0,1), eps >= 0, finite lr and weight_decay).
+ * Everything else (pointers, alignment, ordering, first-call behaviour) is as for adam_mini_step.
+ */
+enum { ADAM_MINI_STEP_ADVANCE = 1u };
+int adam_mini_step_device_hparams(adam_mini_layout* layout, void* const* params,
+                                  const void* const* grads, void* const* exp_avg, float* v_dev,
+                                  adam_mini_hparams* hp_dev, uint32_t flags, void* hip_stream);
+
+/*
  * The same step for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * same results bit for bit, same validation as adam_mini_step; but the work tables,

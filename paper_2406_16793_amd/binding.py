@@ -54,7 +54,7 @@ _lib = None
 
 EXPORTS = ["adam_mini_init_layout", "adam_mini_num_blocks", "adam_mini_num_tensors",
            "adam_mini_export_layout", "adam_mini_block_id", "adam_mini_write_block_ids",
-           "adam_mini_step", "adam_mini_step_static", "adam_mini_set_option", "adam_mini_num_buckets",
+           "adam_mini_step", "adam_mini_step_static", "adam_mini_step_device_hparams", "adam_mini_set_option", "adam_mini_num_buckets",
            "adam_mini_profile_enable", "adam_mini_profile_read", "adam_mini_destroy_layout",
            "adam_mini_strerror", "adam_mini_last_hip_error"]
 
@@ -94,6 +94,9 @@ def load(path: Optional[str] = None):
                                    ctypes.POINTER(HParams), vp]
     lib.adam_mini_step_static.restype = i32
     lib.adam_mini_step_static.argtypes = lib.adam_mini_step.argtypes
+    lib.adam_mini_step_device_hparams.restype = i32
+    lib.adam_mini_step_device_hparams.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                                  vp, u32, vp]
     lib.adam_mini_num_buckets.restype = u32
     lib.adam_mini_num_buckets.argtypes = [vp]
     lib.adam_mini_profile_enable.restype = i32
@@ -182,6 +185,17 @@ def adam_mini_step_static(layout: int, params, grads, exp_avg, v_dev_ptr: int, h
                                         ctypes.byref(hp), ctypes.c_void_p(stream)), "adam_mini_step_static")
 
 
+STEP_ADVANCE = 1
+
+
+def adam_mini_step_device_hparams(layout: int, params, grads, exp_avg, v_dev_ptr: int, hp_dev_ptr: int,
+                                  flags: int = 0, stream: int = 0) -> None:
+    """hp_dev_ptr: device pointer to one HParams (32 bytes).  flags: STEP_ADVANCE or 0."""
+    _check(load().adam_mini_step_device_hparams(layout, params, grads, exp_avg, ctypes.c_void_p(v_dev_ptr),
+                                                ctypes.c_void_p(hp_dev_ptr), int(flags), ctypes.c_void_p(stream)),
+           "adam_mini_step_device_hparams")
+
+
 def adam_mini_num_buckets(layout: int) -> int:
     return int(load().adam_mini_num_buckets(layout))
 
@@ -200,6 +214,13 @@ def adam_mini_profile_read(layout: int) -> List[dict]:
 
 def adam_mini_destroy_layout(layout: int) -> None:
     load().adam_mini_destroy_layout(layout)
+
+
+def device_hparams(lr, beta1, beta2, eps, weight_decay, step: int, device: int = 0):
+    """One HParams record in GPU memory (a 32-byte torch tensor): marshalling only."""
+    import torch
+    raw = bytes(HParams(lr, beta1, beta2, eps, weight_decay, step))
+    return torch.frombuffer(bytearray(raw), dtype=torch.uint8).to("cuda:%d" % device)
 
 
 # ---- convenience holder ------------------------------------------------------
@@ -256,6 +277,16 @@ class AdamMini:
         hp = HParams(lr, beta1, beta2, eps, weight_decay, step)
         entry = adam_mini_step_static if static else adam_mini_step
         entry(self.layout, self._ptrs[0], self._ptrs[1], self._ptrs[2], self._ptrs[3], hp, stream)
+
+    def step_device_hparams(self, hp_dev, advance: bool = True, stream: Optional[int] = None) -> None:
+        """hp_dev: a torch uint8 tensor of 32 bytes on the GPU holding one HParams (see device_hparams())."""
+        import torch
+        if self._ptrs is None:
+            raise RuntimeError("bind() the tensors first")
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        adam_mini_step_device_hparams(self.layout, self._ptrs[0], self._ptrs[1], self._ptrs[2], self._ptrs[3],
+                                      hp_dev.data_ptr(), STEP_ADVANCE if advance else 0, stream)
 
     def block_ids(self, tensor: int):
         import torch

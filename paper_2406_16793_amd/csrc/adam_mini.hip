@@ -63,6 +63,7 @@ struct AmDeviceMem {
                                // of the second work-item numbering (column-block update pass)
   float* partials = nullptr;   // LARGE: one float per chunk; STRIDED: [row chunks][columns] per tensor
   float* scales = nullptr;     // LARGE: one step scale per large block; STRIDED: one per column
+  AmScalars* scalars = nullptr;  // the step's scalars of adam_mini_step_device_hparams
 };
 
 // The pointer lists a segment table currently holds.
@@ -191,7 +192,7 @@ int64_t row_cap(const AmBucket& bk, int teams, size_t grad_bytes, const AmTuning
 }
 
 template <typename G, int VEC>
-int launch_row(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+int launch_row(const AmBucket& bk, const AmTable& tab, float* v, const AmScalarsArg& sc, const AmCtx& cx) {
   const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
 #define X(L, U)                                                                                       \
@@ -226,7 +227,7 @@ int launch_row_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, uint
 }
 
 template <typename G, int VEC>
-int launch_row_lds(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+int launch_row_lds(const AmBucket& bk, const AmTable& tab, float* v, const AmScalarsArg& sc, const AmCtx& cx) {
   if constexpr (VEC == 1) {
     return ADAM_MINI_INVALID_ARG;  // the layout builder never stages scalar-unit blocks
   } else {
@@ -265,7 +266,7 @@ AmTable second_numbering(const AmTable& tab, const uint32_t* keys_base, uint64_t
 }
 
 template <typename G, int VEC, int CPL>
-int launch_strided_cpl(const AmBucket& bk, const AmTable& tab, const AmTable& tab2, float* v, const AmScalars& sc,
+int launch_strided_cpl(const AmBucket& bk, const AmTable& tab, const AmTable& tab2, float* v, const AmScalarsArg& sc,
                        const AmCtx& cx) {
   if constexpr (!am_strided_ok<G, VEC, CPL>()) {
     return ADAM_MINI_INVALID_ARG;
@@ -287,7 +288,7 @@ int launch_strided_cpl(const AmBucket& bk, const AmTable& tab, const AmTable& ta
 }
 
 template <typename G, int VEC>
-int launch_strided(const AmBucket& bk, const AmTable& tab, const AmTable& tab2, float* v, const AmScalars& sc,
+int launch_strided(const AmBucket& bk, const AmTable& tab, const AmTable& tab2, float* v, const AmScalarsArg& sc,
                    const AmCtx& cx) {
   if (bk.var.upt <= 0) return ADAM_MINI_INVALID_ARG;
   if (bk.var.aux == 2) return launch_strided_cpl<G, VEC, 2>(bk, tab, tab2, v, sc, cx);
@@ -338,7 +339,7 @@ std::vector<AmSlice> large_slices(const AmBucket& bk, size_t grad_bytes, const A
 }
 
 template <typename G, int VEC>
-int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScalarsArg& sc, const AmCtx& cx) {
   const AmVariant& var = bk.var;
   float* partials = cx.mem.partials;
   float* scales = cx.mem.scales;
@@ -387,7 +388,7 @@ int launch_large_ids(const AmBucket& bk, const AmTable& tab, uint32_t tensor, ui
 }
 
 template <typename G, int VEC>
-int launch_elementwise(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+int launch_elementwise(const AmBucket& bk, const AmTable& tab, float* v, const AmScalarsArg& sc, const AmCtx& cx) {
   const AmVariant& var = bk.var;
   const uint32_t n_items = (uint32_t)bk.n_items;
   const uint32_t grid = grid_for(bk.n_items, cx.t);
@@ -418,7 +419,7 @@ int launch_elementwise_ids(const AmBucket& bk, const AmTable& tab, uint32_t tens
 }
 
 template <typename G, int VEC>
-int launch_fused(const AmBucket& bk, const AmTable& tab, float* v, const AmScalars& sc, const AmCtx& cx) {
+int launch_fused(const AmBucket& bk, const AmTable& tab, float* v, const AmScalarsArg& sc, const AmCtx& cx) {
   if constexpr (VEC != 4) {
     return ADAM_MINI_INVALID_ARG;  // the layout builder fuses lists of whole 4-element units only
   } else {
@@ -491,7 +492,7 @@ AmTable bucket_table(const adam_mini_layout* L, const AmDeviceMem& mem, const Am
   return tab;
 }
 
-int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, const AmScalars& sc,
+int launch_bucket_step(const adam_mini_layout* L, const AmBucket& bk, float* v, const AmScalarsArg& sc,
                        const AmCtx& cx) {
   const AmTable tab = bucket_table(L, cx.mem, bk);
   return dispatch_grad(L->host.grad_dtype, bk.var.vec, [&](auto tag) {
@@ -547,7 +548,7 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Byte layout of the work tables inside one allocation (or inside the static scratch).
 struct AmTableBytes {
-  size_t segs = 0, keys = 0, partials = 0, scales = 0, total = 0;  // offsets, then the size
+  size_t segs = 0, keys = 0, partials = 0, scales = 0, scalars = 0, total = 0;  // offsets, then the size
 };
 
 AmTableBytes table_bytes(const AmHostLayout& h) {
@@ -556,7 +557,8 @@ AmTableBytes table_bytes(const AmHostLayout& h) {
   b.keys = round_up(h.n_segs * sizeof(AmSeg), 256);
   b.partials = b.keys + round_up(3 * h.n_segs * sizeof(uint32_t), 256);
   b.scales = b.partials + round_up(h.n_partials * sizeof(float), 256);
-  b.total = b.scales + round_up(h.n_lblocks * sizeof(float), 256);
+  b.scalars = b.scales + round_up(h.n_lblocks * sizeof(float), 256);
+  b.total = b.scalars + 256;  // one AmScalars: the step's scalars when the hyper-parameters live on the device
   return b;
 }
 
@@ -566,6 +568,7 @@ AmDeviceMem carve(unsigned char* base, const AmTableBytes& b) {
   m.keys = reinterpret_cast<uint32_t*>(base + b.keys);
   m.partials = reinterpret_cast<float*>(base + b.partials);
   m.scales = reinterpret_cast<float*>(base + b.scales);
+  m.scalars = reinterpret_cast<AmScalars*>(base + b.scalars);
   return m;
 }
 
@@ -711,9 +714,8 @@ AmScalars step_scalars(const adam_mini_hparams* hp) {
 }
 
 // The launches of one step, with the tables and scratch of `mem`.
-int launch_step(adam_mini_layout* layout, const AmDeviceMem& mem, float* v_dev, const adam_mini_hparams* hp,
+int launch_step(adam_mini_layout* layout, const AmDeviceMem& mem, float* v_dev, const AmScalarsArg& sc,
                 hipStream_t stream) {
-  const AmScalars sc = step_scalars(hp);
   const AmCtx cx{layout->host.tuning, stream, layout->lds_per_cu, mem};
   const size_t nb = layout->host.buckets.size();
   const bool timed = layout->profile_used < layout->profile_capacity;
@@ -905,7 +907,35 @@ int adam_mini_step(adam_mini_layout* layout, void* const* params, const void* co
     if (rc != ADAM_MINI_OK) return rc;
     layout->cache.keep(params, grads, exp_avg, n);
   }
-  return launch_step(layout, layout->mem, v_dev, hp, stream);
+  return launch_step(layout, layout->mem, v_dev, AmScalarsArg{step_scalars(hp), nullptr}, stream);
+}
+
+int adam_mini_step_device_hparams(adam_mini_layout* layout, void* const* params, const void* const* grads,
+                                  void* const* exp_avg, float* v_dev, adam_mini_hparams* hp_dev, uint32_t flags,
+                                  void* hip_stream) {
+  // host-side checks as for adam_mini_step, with stand-in hyper-parameters: the real ones cannot be read here
+  if (!hp_dev || (flags & ~(uint32_t)ADAM_MINI_STEP_ADVANCE) != 0) return ADAM_MINI_INVALID_ARG;
+  if (((uintptr_t)hp_dev & 7u) != 0) return ADAM_MINI_MISALIGNED;
+  const adam_mini_hparams stand_in{1e-3f, 0.9f, 0.95f, 1e-8f, 0.0f, 1};
+  int rc = validate_step(layout, params, grads, exp_avg, v_dev, &stand_in);
+  if (rc != ADAM_MINI_OK) return rc;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  DeviceGuard guard;
+  rc = guard.enter(layout->device);
+  if (rc != ADAM_MINI_OK) return rc;
+  rc = ensure_device_state(layout);
+  if (rc != ADAM_MINI_OK) return rc;
+  const size_t n = layout->host.tensors.size();
+  if (!layout->cache.same(params, grads, exp_avg, n)) {
+    layout->cache.valid = false;
+    rc = write_pointers(layout, params, grads, exp_avg, stream);
+    if (rc != ADAM_MINI_OK) return rc;
+    layout->cache.keep(params, grads, exp_avg, n);
+  }
+  static_assert(sizeof(AmDeviceHparams) == sizeof(adam_mini_hparams), "device view of adam_mini_hparams");
+  hipLaunchKernelGGL(am_prepare_scalars, dim3(1), dim3(64), 0, stream, reinterpret_cast<AmDeviceHparams*>(hp_dev),
+                     (uint32_t)((flags & ADAM_MINI_STEP_ADVANCE) != 0), layout->mem.scalars);
+  return launch_step(layout, layout->mem, v_dev, AmScalarsArg{AmScalars{}, layout->mem.scalars}, stream);
 }
 
 int adam_mini_step_static(adam_mini_layout* layout, void* const* params, const void* const* grads,
@@ -946,7 +976,7 @@ int adam_mini_step_static(adam_mini_layout* layout, void* const* params, const v
     layout->static_cache.keep(params, grads, exp_avg, n);
     g_scratch_owner[layout->device] = layout->uid;
   }
-  return launch_step(layout, mem, v_dev, hp, stream);
+  return launch_step(layout, mem, v_dev, AmScalarsArg{step_scalars(hp), nullptr}, stream);
 }
 
 uint32_t adam_mini_num_buckets(const adam_mini_layout* layout) {

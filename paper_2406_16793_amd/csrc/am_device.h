@@ -297,6 +297,12 @@ __device__ __forceinline__ uint32_t am_find_seg(const uint32_t* __restrict__ key
   return lo;
 }
 
+// The step's scalars: the launch argument itself, or the copy in device memory it points to (a uniform
+// choice, and a scalar load: every lane of every workgroup reads the same 32 bytes).
+__device__ __forceinline__ AmScalars am_scalars(const AmScalarsArg& a) {
+  return a.dev ? *a.dev : a.val;
+}
+
 // ---------------------------------------------------------------------------
 // the arithmetic of Algorithm 1 (Section 2.3), fp32
 // ---------------------------------------------------------------------------

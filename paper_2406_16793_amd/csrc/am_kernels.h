@@ -85,6 +85,39 @@ __global__ __launch_bounds__(256) void am_write_pointers(AmSeg* __restrict__ seg
 }
 
 // ===========================================================================
+// hyper-parameters that live on the device: one thread turns them into the step's scalars, in double
+// like the host does for an ordinary step, optionally advancing the step counter first (so that a
+// captured graph of  prepare + step  replays as the NEXT step each time).  Layout of `hp`: the public
+// adam_mini_hparams { float lr, beta1, beta2, eps, weight_decay; uint64_t step; }.
+// ===========================================================================
+struct AmDeviceHparams {
+  float lr, beta1, beta2, eps, weight_decay;
+  unsigned long long step;
+};
+
+__global__ __launch_bounds__(64) void am_prepare_scalars(AmDeviceHparams* __restrict__ hp, uint32_t advance,
+                                                         AmScalars* __restrict__ out) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  unsigned long long t = hp->step;
+  if (advance) {
+    t += 1;
+    hp->step = t;
+  }
+  const double b1 = hp->beta1, b2 = hp->beta2;
+  const double bc1 = 1.0 - pow(b1, (double)t), bc2 = 1.0 - pow(b2, (double)t);
+  AmScalars sc;
+  sc.beta1 = hp->beta1;
+  sc.omb1 = (float)(1.0 - b1);
+  sc.beta2 = hp->beta2;
+  sc.omb2 = (float)(1.0 - b2);
+  sc.eps = hp->eps;
+  sc.bc2 = (float)bc2;
+  sc.step_size = (float)((double)hp->lr / bc1);
+  sc.lr_wd = (float)((double)hp->lr * (double)hp->weight_decay);
+  *out = sc;
+}
+
+// ===========================================================================
 // ROW family
 // ===========================================================================
 template <int LANES>
@@ -141,7 +174,8 @@ __device__ __forceinline__ uint64_t am_row_unit(int k, uint32_t blocked) {
 template <typename G, int VEC, int LANES, int UPT>
 __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_kernel(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                       uint32_t blocked, float* __restrict__ v,
-                                                                      AmScalars sc) {
+                                                                      AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   using Geom = AmRowGeom<LANES>;
   // slot [parity][w] = sum of wavefront w; slot [parity][WAVES] = the block's old v
   __shared__ float xch[2][(Geom::WAVES > 1 ? Geom::WAVES : 1) + 1];
@@ -281,7 +315,8 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_KERNEL_PAR
 
 template <typename G, int VEC>
 __global__ __launch_bounds__(kFusedThreads) void am_fused_kernel(AM_KERNEL_PARAMS, uint32_t n_items,
-                                                                 float* __restrict__ v, AmScalars sc) {
+                                                                 float* __restrict__ v, AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   constexpr int WAVES = kFusedThreads / 64;
   __shared__ float xch[WAVES];     // wavefront results
   __shared__ float xch_v[WAVES];   // a team's old v, left by the team's first wavefront
@@ -461,7 +496,8 @@ __device__ __forceinline__ uint64_t am_lds_unit(uint64_t i, int j) {
 
 template <typename G, int VEC>
 __global__ __launch_bounds__(kLdsRowThreads) void am_row_lds_kernel(AM_KERNEL_PARAMS, uint32_t n_items,
-                                                                    float* __restrict__ v, AmScalars sc) {
+                                                                    float* __restrict__ v, AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   using Raw = typename AmRaw<G, VEC>::T;
   extern __shared__ __attribute__((aligned(16))) unsigned char am_stage_bytes[];
   Raw* stage = reinterpret_cast<Raw*>(am_stage_bytes);
@@ -693,7 +729,8 @@ __global__ __launch_bounds__(256) void am_large_partial(AM_KERNEL_PARAMS, uint32
 __global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS, uint32_t lblock_base,
                                                          uint32_t n_lblocks, const float* __restrict__ partials,
                                                          float* __restrict__ v, float* __restrict__ scales,
-                                                         AmScalars sc) {
+                                                         AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   // large blocks [lblock_base, lblock_base + n_lblocks) of the bucket
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t waves_per_grid = gridDim.x * 4;
@@ -725,7 +762,8 @@ __global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS, uint3
 template <typename G, int VEC, int THREADS, int UPT>
 __global__ __launch_bounds__(THREADS) void am_large_update(AM_KERNEL_PARAMS, uint32_t item_base,
                                                            uint32_t n_items, uint32_t keep_g,
-                                                           const float* __restrict__ scales, AmScalars sc) {
+                                                           const float* __restrict__ scales, AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
     const uint32_t item = item_base + am_xcd_swizzle(grp, n_items, xcd_code);
     const AmChunkItem it = am_chunk_decode(AM_TABLE_ARGS, item, THREADS * UPT);
@@ -875,7 +913,8 @@ __global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uin
                                                            uint32_t rows_per_item,
                                                            const float* __restrict__ partials,
                                                            float* __restrict__ v, float* __restrict__ scales,
-                                                           AmScalars sc) {
+                                                           AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   for (uint32_t gc = blockIdx.x * 256 + threadIdx.x; gc < n_cols; gc += gridDim.x * 256) {
     const uint32_t s = am_find_seg(lblock_keys, n_segs, gc);
     const AmSeg& S = segs[s];
@@ -908,7 +947,8 @@ __global__ __launch_bounds__(256) void am_strided_finalize(AM_KERNEL_PARAMS, uin
 template <typename G, int VEC>
 __global__ __launch_bounds__(kStridedThreads) void am_strided_update(AM_KERNEL_PARAMS, uint32_t n_items,
                                                                      const float* __restrict__ scales,
-                                                                     AmScalars sc) {
+                                                                     AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   constexpr int UPT = kStridedUpdateUpt;
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
     const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
@@ -1000,7 +1040,8 @@ __device__ __forceinline__ AmTileItem am_tile_decode(AM_TABLE_PARAMS, uint32_t i
 
 template <typename G, int VEC, int THREADS, int UPT>
 __global__ __launch_bounds__(THREADS) void am_elementwise(AM_KERNEL_PARAMS,
-                                                          uint32_t n_items, float* __restrict__ v, AmScalars sc) {
+                                                          uint32_t n_items, float* __restrict__ v, AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
   for (uint32_t grp = blockIdx.x; grp < n_items; grp += gridDim.x) {
     const uint32_t item = am_xcd_swizzle(grp, n_items, xcd_code);
     const AmTileItem it = am_tile_decode(AM_TABLE_ARGS, item, THREADS * UPT);

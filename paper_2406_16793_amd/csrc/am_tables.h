@@ -77,6 +77,14 @@ struct AmScalars {
   float lr_wd;      // lr * weight_decay
 };
 
+// How the per-step scalars reach a kernel: by value (computed on the host for this call), or -- dev not
+// null -- read from device memory, where a small kernel put them from hyper-parameters that live on the
+// device (a step that a HIP graph can replay with an advancing step counter).
+struct AmScalarsArg {
+  AmScalars val;
+  const AmScalars* dev;
+};
+
 // Variant of a kernel family: how a block (or tile) is spread over threads.
 struct AmVariant {
   int family;  // AmFamily

@@ -309,3 +309,19 @@ def test_small_lists_take_one_launch_only_when_that_saves_launches():
         assert kinds([rows, heads, gains])[1] == 2      # 16-lane teams for the rows and the gains, a 1024-lane team for the heads
     finally:
         B.adam_mini_set_option("reset", 0)
+
+
+def test_device_hparams_step_validates_on_the_host_what_it_can():
+    h = B.adam_mini_init_layout([(16, 4, 1.0)], B.GRAD_F32, -1)
+    lib = B.load()
+    P = B.pointer_array([0x1000])
+    call = lambda p, v, hp, flags: lib.adam_mini_step_device_hparams(h, p, P, P, ctypes.c_void_p(v), ctypes.c_void_p(hp),
+                                                                     flags, None)
+    assert call(P, 0x1000, 0x2000, 0) == B.NO_DEVICE          # everything checkable passed
+    assert call(P, 0x1000, 0, 0) == B.INVALID_ARG             # null hyper-parameter pointer
+    assert call(P, 0x1000, 0x2004, 0) == B.MISALIGNED
+    assert call(P, 0x1000, 0x2000, 2) == B.INVALID_ARG        # unknown flag
+    assert call(P, 0x1004, 0x2000, 0) == B.MISALIGNED
+    assert call(None, 0x1000, 0x2000, 1) == B.INVALID_ARG
+    B.adam_mini_destroy_layout(h)
+    assert ctypes.sizeof(B.HParams) == 32

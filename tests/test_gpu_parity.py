@@ -591,3 +591,65 @@ def test_moving_gradient_buffers_cost_no_host_wait():
     assert still_running, "the host waited for the stream inside adam_mini_step"
     fixed.close()
     moving.close()
+
+
+def test_step_with_device_hyperparameters_replays_as_consecutive_steps():
+    """adam_mini_step_device_hparams: lr, betas and the step counter live in device memory, the counter
+    advances on the device, so ONE captured graph performs steps 2, 3, 4, 5 on successive replays (with
+    new gradients in the same buffers and lr rewritten on the device before step 4).  The result must
+    match the oracle, and the ordinary host-hyper-parameter steps to rounding of the bias corrections."""
+    import ctypes
+    import gpu_harness as H
+    import torch
+    import oracle as orc
+    from paper_2406_16793_amd import binding as B
+    shapes = [(64, 4096), (3, 49152), (2, 524288), (500, 128), (40, 1), (7, 333), (3, 32768)]
+    specs = _wl(shapes, "bf16").specs + H.make_specs([(512, 96)], strided=True)
+    host_run, dev_run = H.GpuRun(specs, "bf16"), H.GpuRun(specs, "bf16")
+    torch.manual_seed(21)
+    p0 = [torch.randn(s.numel) * 0.02 for s in specs]
+    grads = [[(torch.randn(s.numel) * 1e-3).to(torch.bfloat16) for s in specs] for _ in range(5)]
+    for k in range(len(specs)):
+        host_run.p[k].copy_(p0[k])
+        dev_run.p[k].copy_(p0[k])
+    st = orc.OracleState([s.numel for s in specs], [s.block_numel for s in specs], [s.wd_scale for s in specs],
+                         [x.numpy() for x in p0], strided=[s.strided for s in specs])
+    lrs = [1e-3, 1e-3, 1e-3, 4e-4, 4e-4]
+    hp = dict(beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    for t in range(1, 6):
+        for k in range(len(specs)):
+            host_run.g[k].copy_(grads[t - 1][k])
+        host_run.opt.step(step=t, lr=lrs[t - 1], **hp)
+        st.step([H.grad_to_host(g) for g in grads[t - 1]], orc.Hyper.from_f32(lr=lrs[t - 1], **hp))
+    torch.cuda.synchronize()
+
+    hp_dev = B.device_hparams(lrs[0], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"], 0)   # t starts at 0
+    for k in range(len(specs)):
+        dev_run.g[k].copy_(grads[0][k])
+    dev_run.opt.step_device_hparams(hp_dev, advance=True)       # eager: step 1, creates the device tables
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dev_run.opt.step_device_hparams(hp_dev, advance=True)   # captured, not executed
+    for t in range(2, 6):
+        for k in range(len(specs)):
+            dev_run.g[k].copy_(grads[t - 1][k])
+        if lrs[t - 1] != lrs[t - 2]:
+            new_lr = torch.frombuffer(bytearray(bytes(ctypes.c_float(lrs[t - 1]))), dtype=torch.uint8)
+            hp_dev[0:4].copy_(new_lr)                           # lr is the record's first field
+        graph.replay()
+        torch.cuda.synchronize()
+        x = torch.randn(1 << 18, device="cuda").sum().item()   # unrelated eager work between replays
+        assert x == x
+    raw = bytes(hp_dev.cpu().numpy().tobytes())
+    assert int.from_bytes(raw[24:32], "little") == 5           # the counter advanced on the device
+    worst = H.compare(dev_run, st, 5e-3, label="device hyper-parameters")
+    assert worst < 1e-5
+    same = True
+    for a, b in zip(host_run.p + host_run.m + [host_run.v], dev_run.p + dev_run.m + [dev_run.v]):
+        same = same and torch.equal(a, b)
+        denom = float(a.double().norm())
+        assert float((a.double() - b.double()).norm()) <= 1e-6 * denom + 1e-30
+    print("device-hyper-parameter run bitwise equal to the host-hyper-parameter run: %s" % same, flush=True)
+    host_run.close()
+    dev_run.close()
