@@ -303,41 +303,6 @@ int launch_strided_ids(const AmBucket& bk, const AmTable& tab2, uint32_t tensor,
   return ADAM_MINI_OK;
 }
 
-// One contiguous run of a LARGE bucket's work items and blocks.
-struct AmSlice {
-  uint32_t item_first, n_items, lblock_first, n_lblocks;
-};
-
-// The bucket as one slice, or -- large_slice_mb > 0 -- cut at block boundaries into slices whose gradients
-// are at most that many MB each: partial sums, finalize and update of a slice then run back to back, so the
-// update's second read of the slice's gradient can be served by the memory-side cache instead of HBM.
-std::vector<AmSlice> large_slices(const AmBucket& bk, size_t grad_bytes, const AmTuning& t) {
-  std::vector<AmSlice> out;
-  if (t.large_slice_mb <= 0) {
-    out.push_back(AmSlice{0u, (uint32_t)bk.n_items, 0u, (uint32_t)bk.n_lblocks});
-    return out;
-  }
-  const uint64_t limit = (uint64_t)t.large_slice_mb << 20;
-  AmSlice cur{0u, 0u, 0u, 0u};
-  uint64_t bytes = 0;
-  for (const AmSeg& s : bk.segs) {
-    const uint64_t block_bytes = s.block_numel * grad_bytes;
-    const uint64_t n_blocks = s.row_len;  // LARGE: the tensor's block count
-    for (uint64_t b = 0; b < n_blocks; ++b) {
-      if (cur.n_lblocks > 0 && bytes + block_bytes > limit) {
-        out.push_back(cur);
-        cur = AmSlice{cur.item_first + cur.n_items, 0u, cur.lblock_first + cur.n_lblocks, 0u};
-        bytes = 0;
-      }
-      cur.n_items += s.chunks_per_block;
-      cur.n_lblocks += 1;
-      bytes += block_bytes;
-    }
-  }
-  if (cur.n_lblocks > 0) out.push_back(cur);
-  return out;
-}
-
 template <typename G, int VEC>
 int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScalarsArg& sc, const AmCtx& cx) {
   const AmVariant& var = bk.var;
@@ -347,7 +312,7 @@ int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScala
 #define X(L, U)                                                                                           \
   if constexpr (VEC * U <= 64) { /* larger chunks are never chosen: they would not fit the registers */   \
     if (var.lanes == L && var.upt == U) {                                                                 \
-      for (const AmSlice& sl : large_slices(bk, sizeof(G), cx.t)) {                                       \
+      for (const AmSlice& sl : bk.slices) {                                                               \
         const uint32_t grid = grid_for(sl.n_items, cx.t);                                                 \
         const uint32_t fgrid = grid_for((sl.n_lblocks + 3) / 4, cx.t);                                    \
         const uint32_t pgrid = grid_for((sl.n_items + 3) / 4, cx.t);                                      \
@@ -1042,10 +1007,7 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
     o.upt = bk.var.upt;
     o.n_tensors = (uint32_t)bk.segs.size();
     o.n_kernels = bk.var.family == AM_FAM_STRIDED ? 3u : 1u;
-    if (bk.var.family == AM_FAM_LARGE) {
-      const size_t grad_bytes = layout->host.grad_dtype == ADAM_MINI_GRAD_BF16 ? 2 : 4;
-      o.n_kernels = 3u * (uint32_t)large_slices(bk, grad_bytes, layout->host.tuning).size();
-    }
+    if (bk.var.family == AM_FAM_LARGE) o.n_kernels = 3u * (uint32_t)bk.slices.size();
     o.n_items = bk.n_items;
     for (const AmSeg& s : bk.segs) {
       const AmTensorInfo& ti = layout->host.tensors[s.tensor];

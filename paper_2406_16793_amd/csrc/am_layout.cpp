@@ -52,6 +52,36 @@ bool same_variant(const AmVariant& a, const AmVariant& b) {
 
 }  // namespace
 
+// The LARGE bucket as one slice, or -- large_slice_mb > 0 -- cut at block boundaries into slices whose
+// gradients are at most that many MB each: partial sums, finalize and update of a slice then run back to
+// back (a measurement knob: would the update's second read of a slice's gradient be served on chip?).
+static std::vector<AmSlice> large_slices(const AmBucket& bk, size_t grad_bytes, const AmTuning& t) {
+  std::vector<AmSlice> out;
+  if (t.large_slice_mb <= 0) {
+    out.push_back(AmSlice{0u, (uint32_t)bk.n_items, 0u, (uint32_t)bk.n_lblocks});
+    return out;
+  }
+  const uint64_t limit = (uint64_t)t.large_slice_mb << 20;
+  AmSlice cur{0u, 0u, 0u, 0u};
+  uint64_t bytes = 0;
+  for (const AmSeg& s : bk.segs) {
+    const uint64_t block_bytes = s.block_numel * grad_bytes;
+    const uint64_t n_blocks = s.row_len;  // LARGE: the tensor's block count
+    for (uint64_t b = 0; b < n_blocks; ++b) {
+      if (cur.n_lblocks > 0 && bytes + block_bytes > limit) {
+        out.push_back(cur);
+        cur = AmSlice{cur.item_first + cur.n_items, 0u, cur.lblock_first + cur.n_lblocks, 0u};
+        bytes = 0;
+      }
+      cur.n_items += s.chunks_per_block;
+      cur.n_lblocks += 1;
+      bytes += block_bytes;
+    }
+  }
+  if (cur.n_lblocks > 0) out.push_back(cur);
+  return out;
+}
+
 int am_path_kind(const AmVariant& v) {
   switch (v.family) {
     case AM_FAM_ELEMENTWISE: return ADAM_MINI_PATH_ELEMENTWISE;
@@ -297,6 +327,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     bk.table_offset = out->n_segs;
     out->n_segs += bk.segs.size();
     if (bk.var.family == AM_FAM_LARGE) {
+      bk.slices = large_slices(bk, grad_dtype == ADAM_MINI_GRAD_BF16 ? 2 : 4, tuning);
       if (bk.n_items > out->n_partials) out->n_partials = bk.n_items;
       if (bk.n_lblocks > out->n_lblocks) out->n_lblocks = bk.n_lblocks;
     } else if (bk.var.family == AM_FAM_STRIDED) {

@@ -22,6 +22,11 @@ struct AmTensorInfo {
   int seg;            // index into that bucket's segs
 };
 
+// One contiguous run of a LARGE bucket's work items and blocks: a launch triple of its own.
+struct AmSlice {
+  uint32_t item_first, n_items, lblock_first, n_lblocks;
+};
+
 struct AmBucket {
   AmVariant var;
   std::vector<AmSeg> segs;  // pointers left null here; filled at step time
@@ -32,6 +37,7 @@ struct AmBucket {
   uint64_t n_partials = 0;  // STRIDED: floats of partial sums the bucket needs
   uint64_t table_offset = 0;  // index of segs[0] in the concatenated device table
   uint64_t lds_bytes = 0;     // ROW_LDS: bytes of LDS that hold the largest block's gradient
+  std::vector<AmSlice> slices;  // LARGE: the bucket as one slice, or cut by large_slice_mb (see am_layout.cpp)
   bool alt_reducer = false;   // some tensor's block statistic is not a plain sum of squares (2-norm, max, min)
 };
 

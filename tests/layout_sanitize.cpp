@@ -184,6 +184,15 @@ void check_layout(const std::vector<adam_mini_tensor_desc>& descs, int grad_dtyp
     if (var.family == AM_FAM_LARGE) {
       CHECK(bk.n_lblocks == lblocks, "%s: large blocks", what);
       CHECK(L.n_partials >= bk.n_items && L.n_lblocks >= bk.n_lblocks, "%s: scratch of a large bucket", what);
+      // the slices tile the bucket's items and blocks in order, and respect the byte limit unless one block exceeds it
+      uint64_t it = 0, lb = 0;
+      for (const AmSlice& sl : bk.slices) {
+        CHECK(sl.item_first == it && sl.lblock_first == lb && sl.n_items > 0 && sl.n_lblocks > 0, "%s: slice order", what);
+        it += sl.n_items;
+        lb += sl.n_lblocks;
+      }
+      CHECK(it == bk.n_items && lb == bk.n_lblocks, "%s: slices cover %" PRIu64 " of %" PRIu64 " items", what, it, bk.n_items);
+      if (tuning.large_slice_mb <= 0) CHECK(bk.slices.size() == 1, "%s: unsliced bucket in %zu slices", what, bk.slices.size());
     }
     if (var.family == AM_FAM_STRIDED) {
       CHECK(bk.n_lblocks == lblocks && bk.n_partials == partials, "%s: column scratch", what);
@@ -233,6 +242,7 @@ AmTuning random_tuning(Rng& r) {
   t.strided_rows = r.pick(rows);
   t.fuse_max_params = r.in(0, 3) == 0 ? 0 : (int64_t)r.in(1, 40000000);
   t.fuse_target_items = (int64_t)r.in(1, 2000);
+  t.large_slice_mb = r.in(0, 2) == 0 ? (int64_t)r.in(1, 4) : 0;
   return t;
 }
 
