@@ -224,7 +224,7 @@ int adam_mini_step_device_hparams(adam_mini_layout* layout, void* const* params,
  * library runs on holds its own copy until the process ends), and the tables reach it
  * as arguments of small kernels on hip_stream.  The call makes no hipMalloc, no
  * hipFree, no copy and no other allocating call, on its first use or later.
- * A layout needs  n_tensors * 96 + (partial sums + step scales) * 4  bytes, each part
+ * A layout needs  n_tensors * 116 + (partial sums + step scales) * 4 + 256  bytes, each part
  * rounded up to 256 (partial sums: one per 4096-element chunk of every block that
  * spans several workgroups, or one per column and tile of rows for column blocks);
  * the five benchmark shapes need 0.1 to 2.1 MB.  ADAM_MINI_TOO_LARGE if it does not

@@ -305,9 +305,8 @@ __global__ __launch_bounds__(AmRowGeom<LANES>::WG) void am_row_ids(AM_KERNEL_PAR
 //               (T = 16, 64, 256 or 1024: the smallest that holds the block at kFusedUpt units per lane),
 //               exactly the single-pass scheme of am_row_kernel
 //   tile items  1024 * kFusedUpt units of a tensor whose blocks have one element (AdamW-equivalent)
-// T and the number of blocks per item are properties of the tensor (AmSeg::chunks_per_block = T |
-// blocks per item << 16; 0 marks a tile tensor), so they are uniform over a workgroup and the barrier
-// below is too.  The host picks the blocks per item so that a small list makes no more items than the
+// T and the number of blocks per item are properties of the tensor (AmSeg::team_lanes, 0 marks a tile
+// tensor; AmSeg::blocks_per_item), so they are uniform over a workgroup and the barrier below is too.  The host picks the blocks per item so that a small list makes no more items than the
 // chip has compute units: a launch whose workgroups are all resident at once costs little more than an
 // empty one (about 6 us back to back), a second round of workgroups nearly doubles it; teams beyond the
 // item's blocks simply idle.
@@ -328,7 +327,7 @@ __global__ __launch_bounds__(kFusedThreads) void am_fused_kernel(AM_KERNEL_PARAM
     const uint32_t s = am_find_seg(item_keys, n_segs, item);
     const AmSeg& S = segs[s];
     const uint32_t local = item - item_keys[s];
-    const uint32_t T = S.chunks_per_block & 0xffffu, per_item = S.chunks_per_block >> 16;
+    const uint32_t T = S.team_lanes, per_item = S.blocks_per_item;
     const float decay = sc.lr_wd * S.wd_scale;
     float gv[kFusedUpt][VEC], mv[kFusedUpt][VEC], pv[kFusedUpt][VEC];
 
@@ -371,7 +370,7 @@ __global__ __launch_bounds__(kFusedThreads) void am_fused_kernel(AM_KERNEL_PARAM
     // row item: team `threadIdx.x / T` takes block local * per_item + team, if the item has that many
     const uint32_t team = threadIdx.x / T, lane = threadIdx.x % T;
     const uint64_t block = (uint64_t)local * per_item + team;
-    const bool active = team < per_item && block < S.row_len;   // row_len holds the tensor's block count here
+    const bool active = team < per_item && block < S.n_blocks;
     const uint64_t units = S.units_per_block;
     const uint64_t elem0 = block * S.block_numel;
     const uint64_t v_idx = S.v_first + block;
@@ -455,7 +454,7 @@ __global__ __launch_bounds__(kFusedThreads) void am_fused_ids(AM_KERNEL_PARAMS, 
     const AmSeg& S = segs[s];
     if (S.tensor != tensor) continue;
     const uint32_t local = item - item_keys[s];
-    const uint32_t T = S.chunks_per_block & 0xffffu, per_item = S.chunks_per_block >> 16;
+    const uint32_t T = S.team_lanes, per_item = S.blocks_per_item;
     if (T == 0) {
       const uint64_t unit0 = (uint64_t)local * (kFusedThreads * kFusedUpt);
 #pragma unroll
@@ -469,7 +468,7 @@ __global__ __launch_bounds__(kFusedThreads) void am_fused_ids(AM_KERNEL_PARAMS, 
     }
     const uint32_t team = threadIdx.x / T, lane = threadIdx.x % T;
     const uint64_t block = (uint64_t)local * per_item + team;
-    if (team >= per_item || block >= S.row_len) continue;
+    if (team >= per_item || block >= S.n_blocks) continue;
 #pragma unroll
     for (int k = 0; k < kFusedUpt; ++k) {
       const uint64_t u = lane + (uint64_t)k * T;

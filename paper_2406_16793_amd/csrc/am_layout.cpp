@@ -66,7 +66,7 @@ static std::vector<AmSlice> large_slices(const AmBucket& bk, size_t grad_bytes, 
   uint64_t bytes = 0;
   for (const AmSeg& s : bk.segs) {
     const uint64_t block_bytes = s.block_numel * grad_bytes;
-    const uint64_t n_blocks = s.row_len;  // LARGE: the tensor's block count
+    const uint64_t n_blocks = s.n_blocks;
     for (uint64_t b = 0; b < n_blocks; ++b) {
       if (cur.n_lblocks > 0 && bytes + block_bytes > limit) {
         out.push_back(cur);
@@ -247,6 +247,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
     s.item_first = (uint32_t)bk.n_items;
     s.block_numel = d.block_numel;
     s.chunks_per_block = 1;
+    s.n_blocks = ti.n_blocks;
     s.lblock_first = (uint32_t)bk.n_lblocks;
     s.tensor = k;
     s.wd_scale = d.wd_scale;
@@ -257,7 +258,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       if (d.block_numel == 1) {
         s.block_numel = d.numel;
         s.units_per_block = d.numel / 4;
-        s.chunks_per_block = 0;
+        s.team_lanes = 0;
         items = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
       } else {
         s.units_per_block = d.block_numel / 4;
@@ -269,8 +270,8 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
         const uint64_t cap = (uint64_t)kFusedThreads / team;
         if (per_item > cap) per_item = cap;
         if (per_item < 1) per_item = 1;
-        s.chunks_per_block = team | ((uint32_t)per_item << 16);
-        s.row_len = ti.n_blocks;
+        s.team_lanes = team;
+        s.blocks_per_item = (uint32_t)per_item;
         items = (ti.n_blocks + per_item - 1) / per_item;
       }
     } else if (var.family == AM_FAM_ELEMENTWISE) {
@@ -303,7 +304,6 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       const uint64_t cpb = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
       if (cpb >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
       s.chunks_per_block = (uint32_t)cpb;
-      s.row_len = ti.n_blocks;
       items = ti.n_blocks * cpb;
       bk.n_lblocks += ti.n_blocks;
     }

@@ -29,12 +29,15 @@ struct AmSeg {
   uint64_t units_per_block;  // block_numel / VEC (ELEMENTWISE: ceil(numel / VEC))
   uint32_t item_first;    // number of work items of the bucket before this tensor
   uint32_t lblock_first;  // LARGE: number of large blocks of the bucket before this tensor
-  uint32_t chunks_per_block; // LARGE: work items per block; FUSED: lanes of the team that holds a block | blocks per work item << 16 (0: one-element blocks); otherwise 1
+  uint32_t chunks_per_block; // LARGE: work items per block; STRIDED: column groups per row chunk; otherwise 1
   uint32_t tensor;        // index in the caller's tensor list
   float wd_scale;         // lambda_k = weight_decay * wd_scale
   uint32_t reducer;       // block statistic of g .* g that feeds v: 0 mean (the method), 1 1-norm, 2 2-norm, 3 max, 4 min
   uint64_t aux;           // STRIDED: index of the tensor's first partial sum in the scratch
-  uint64_t row_len;       // STRIDED: elements per stored row (= number of blocks C); LARGE, FUSED: number of blocks
+  uint64_t row_len;       // STRIDED: elements per stored row (= number of blocks C)
+  uint64_t n_blocks;      // number of blocks of the tensor
+  uint32_t team_lanes;    // FUSED: lanes of the team that holds one block (16, 64, 256, 1024); 0: one-element blocks
+  uint32_t blocks_per_item;  // FUSED: whole blocks per work item (<= 1024 / team_lanes)
 };
 // STRIDED reuses the fields as: block_numel = rows R of the stored [R, C] matrix (elements per block),
 // units_per_block = units per ROW (C / VEC), chunks_per_block = column groups per row chunk,
@@ -60,8 +63,8 @@ constexpr int kStridedThreads = 256;
 constexpr int kStridedUpdateUpt = 4;
 
 // Workgroup of the FUSED family, shared by the layout builder and the kernel: 1024 threads; a block is
-// held by a team of 16, 64, 256 or 1024 of them at up to kFusedUpt units per lane (AmSeg::chunks_per_block
-// holds the team size and, shifted left by 16, the blocks per work item; 0 for a tensor of one-element blocks; AmSeg::row_len holds the number of blocks).
+// held by a team of 16, 64, 256 or 1024 of them at up to kFusedUpt units per lane (AmSeg::team_lanes; 0 for a
+// tensor of one-element blocks), AmSeg::blocks_per_item whole blocks to a work item.
 constexpr int kFusedThreads = 1024;
 constexpr int kFusedUpt = 4;
 

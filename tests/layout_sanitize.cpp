@@ -86,6 +86,7 @@ void check_layout(const std::vector<adam_mini_tensor_desc>& descs, int grad_dtyp
       CHECK(s.v_first == ti.v_first, "%s: v_first of segment", what);
       CHECK(s.wd_scale == d.wd_scale, "%s: wd_scale", what);
       CHECK(s.reducer == ((d.flags & ADAM_MINI_REDUCE_MASK) >> 4), "%s: reducer", what);
+      CHECK(s.n_blocks == ti.n_blocks, "%s: block count of segment", what);
       const uint64_t vec = (uint64_t)var.vec;
       uint64_t seg_items = 0;
       switch (var.family) {
@@ -160,16 +161,15 @@ void check_layout(const std::vector<adam_mini_tensor_desc>& descs, int grad_dtyp
           CHECK(L.buckets.size() == 1, "%s: a fused list has one bucket", what);
           if (d.block_numel == 1) {
             CHECK(d.numel % 4 == 0 && ti.v_first % 4 == 0, "%s: fused one-element blocks need whole units and an aligned v slice", what);
-            CHECK(s.chunks_per_block == 0 && s.block_numel == d.numel && s.units_per_block * 4 == d.numel, "%s: fused tile tensor", what);
+            CHECK(s.team_lanes == 0 && s.block_numel == d.numel && s.units_per_block * 4 == d.numel, "%s: fused tile tensor", what);
             seg_items = ceil_div(s.units_per_block, (uint64_t)kFusedThreads * kFusedUpt);
           } else {
-            const uint64_t team = s.chunks_per_block & 0xffffu, per_item = s.chunks_per_block >> 16;
+            const uint64_t team = s.team_lanes, per_item = s.blocks_per_item;
             CHECK(team == 16 || team == 64 || team == 256 || team == 1024, "%s: fused team of %" PRIu64, what, team);
             CHECK(per_item >= 1 && per_item * team <= (uint64_t)kFusedThreads, "%s: %" PRIu64 " blocks per fused item", what, per_item);
             CHECK(d.block_numel % 4 == 0 && s.units_per_block * 4 == d.block_numel && s.block_numel == d.block_numel, "%s: fused units", what);
             CHECK(s.units_per_block <= team * kFusedUpt, "%s: fused block of %" PRIu64 " units in a team of %" PRIu64, what, s.units_per_block, team);
             CHECK(team == 16 || s.units_per_block > (team / 4) * kFusedUpt, "%s: fused team larger than needed", what);
-            CHECK(s.row_len == ti.n_blocks, "%s: fused block count", what);
             seg_items = per_item ? ceil_div(ti.n_blocks, per_item) : 0;
           }
           break;
