@@ -8,6 +8,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# where long GPU tests leave their progress log and error summary (a folder that a remote run copies back)
+OUT_DIR = os.environ.get("ADAM_MINI_TEST_OUT", os.path.join(ROOT, "gpurun_out"))
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
@@ -22,8 +26,8 @@ def oracle():
 @pytest.fixture
 def say(capsys):
     """Progress lines that reach the real stdout at once (capture switched off for the print) and a
-    log file under gpurun_out/: a long full-size test must not look hung."""
-    log = os.path.join(ROOT, "gpurun_out", "fullsize_progress.log")
+    log file in the run's output folder: a long full-size test must not look hung."""
+    log = os.path.join(OUT_DIR, "fullsize_progress.log")
 
     def _say(msg):
         with capsys.disabled():

@@ -206,12 +206,12 @@ def run_sampled(wl: workloads.Workload, steps=None, per_tensor=16, large_per_ten
 
 
 def record_error(workload: str, mode: str, worst: float, elements: int, steps: int) -> None:
-    """Keeps the worst normwise relative error of a full-size comparison in gpurun_out/fullsize_errors.json
-    (merged per workload and mode), so the figures survive a quiet pytest run."""
+    """Keeps the worst normwise relative error of a full-size comparison in fullsize_errors.json in the
+    run's output folder (merged per workload and mode), so the figures survive a quiet pytest run."""
     import json
     import os
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    path = os.path.join(root, "gpurun_out", "fullsize_errors.json")
+    from conftest import OUT_DIR
+    path = os.path.join(OUT_DIR, "fullsize_errors.json")
     try:
         os.makedirs(os.path.dirname(path), exist_ok=True)
         data = json.load(open(path)) if os.path.exists(path) else {}

@@ -7,7 +7,7 @@ norm are compared completely.  Besides that the oracle follows a seeded sample o
 tensor of every configuration (blocks never interact, so each sampled block is compared exactly as if
 the oracle had run the whole set), and size-independent properties are checked on everything.  Every
 comparison asserts a normwise relative error below 1e-5 next to the elementwise bound, and leaves its
-worst figure in gpurun_out/fullsize_errors.json."""
+worst figure in fullsize_errors.json in the run's output folder."""
 import pytest
 
 pytestmark = pytest.mark.gpu
