@@ -48,7 +48,7 @@ struct AmTuning {
   int64_t subwave_max_units = 64;   // blocks of <= this many units may use 16-thread teams
   int64_t wave_max_units = 256;     // blocks of <= this many units may use one 64-thread wavefront each
   int64_t team_max_lanes = 1024;    // largest team (threads per block) the row kernel may use
-  int64_t max_upt = 4;              // preferred upper bound on units per thread: the smallest team that
+  int64_t max_upt = 2;              // preferred upper bound on units per thread: the smallest team that
                                     //   stays within it is chosen; exceeded only when no team fits otherwise
   int64_t row_max_units = 1 << 30;  // blocks above this never use the single-pass register kernel
   int64_t lds_max_bytes = 150 * 1024;       // > 0: blocks that do not fit the register kernel and whose gradient fits

@@ -77,7 +77,7 @@ CASES = [
     ("team_max_lanes=256", _o(team_max_lanes=256), BOTH),
     ("team_max_lanes=512", _o(team_max_lanes=512), BOTH),
     ("max_upt=1", _o(max_upt=1), BOTH),
-    ("max_upt=2", _o(max_upt=2), BOTH),
+    ("max_upt=4", _o(max_upt=4), BOTH),
     ("max_upt=3", _o(max_upt=3), BOTH),
     ("max_upt=16", _o(max_upt=16), BOTH),
     ("max_upt=16-wide-waves", _o(max_upt=16, wave_max_units=1024), BOTH),
