@@ -14,22 +14,33 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
 
 
+def _largest_bucket_kernel(workload, adamw=False):
+    """Name of the kernel that serves most parameters of a workload, from a host-only layout."""
+    from paper_2406_16793_amd import binding as B, partition, workloads
+    wl = workloads.get(workload)
+    specs = partition.as_adamw(wl.specs) if adamw else wl.specs
+    h = B.adam_mini_init_layout([(s.numel, s.block_numel, s.wd_scale) for s in specs],
+                                B.GRAD_BF16 if wl.grad_dtype == "bf16" else B.GRAD_F32, -1)
+    buckets = B.adam_mini_profile_read(h)
+    B.adam_mini_destroy_layout(h)
+    top = max(buckets, key=lambda b: b["numel"])
+    return top["kernel"], top["numel"], top["n_blocks"]
+
+
 def test_committed_traffic_summaries_name_the_kernels_bench_reports():
-    """roofline.traffic is looked up by workload and kernel name in profiles/hbm_traffic_<workload>.txt."""
+    """roofline.traffic is looked up by workload and kernel name in profiles/hbm_traffic_<workload>.txt:
+    the committed summaries must hold the kernel that the CURRENT layout builder makes the dominant one."""
     sys.path.insert(0, ROOT)
     import bench
-    for workload, kernel, per_param in (("llama2_7b", "am_row_kernel<am_bf16, 4, 256, 4>", 18),
-                                        ("llama3_8b", "am_row_kernel<am_bf16, 4, 256, 4>", 18),
-                                        ("llama2_13b", "am_row_kernel<float, 4, 512, 3>", 20),
-                                        ("llama2_7b_adamw", "am_elementwise<am_bf16, 4, 256, 4>", 26)):
-        traffic = bench.traffic_from_profiles(workload, kernel)
-        assert traffic is not None and traffic > 1e9, (workload, kernel)
-    # the dominant kernel of the headline workload moves its algorithmic bytes and nothing more
-    from paper_2406_16793_amd import workloads
-    wl = workloads.get("llama2_7b")
-    rows = [s for s in wl.specs if s.block_numel == 4096]
-    algorithmic = sum(s.numel for s in rows) * 18 + 8 * sum(s.n_blocks for s in rows)
-    measured = bench.traffic_from_profiles("llama2_7b", "am_row_kernel<am_bf16, 4, 256, 4>")
-    assert abs(measured / algorithmic - 1.0) < 0.01
+    for workload, adamw, per_param in (("llama2_7b", False, 18), ("llama3_8b", False, 18), ("llama2_13b", False, 20),
+                                       ("llama2_7b", True, 26), ("gpt2_small", False, 20), ("tiny", False, 20)):
+        kernel, numel, n_blocks = _largest_bucket_kernel(workload, adamw)
+        tag = workload + ("_adamw" if adamw else "")
+        traffic, source = bench.traffic_from_profiles(tag, kernel, with_source=True)
+        assert traffic is not None and traffic > 1e7, (tag, kernel)
+        assert source.startswith("profiles/hbm_traffic_%s.txt@" % tag), source       # names the tree it was taken on
+        if workload.startswith("llama"):
+            # the big streaming kernels move their algorithmic bytes and nothing more
+            algorithmic = numel * per_param + (0 if adamw else 8 * n_blocks)
+            assert abs(traffic / algorithmic - 1.0) < 0.01, (tag, kernel, traffic, algorithmic)
     assert bench.traffic_from_profiles("llama2_7b", "no_such_kernel") is None
-    assert json.dumps({"traffic": measured})
