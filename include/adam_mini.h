@@ -306,7 +306,8 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *                        is oversubscribed); 0 = no cap
  *   "row_wg_per_cu"      > 0: fixed cap on resident row-kernel workgroups per compute unit instead
  *   "row_blocked"        1: each wavefront of a row team owns a contiguous span of the block
- *   "stream_wg_per_cu"   the same cap for the AdamW-equivalent and large-block update kernels
+ *   "stream_wg_per_cu"   the same cap for the large-block update kernel
+ *   "ew_wg_per_cu"       the same cap for the AdamW-equivalent kernel
  *   "strided_wg_per_cu"  the same cap for the column-block (ADAM_MINI_FLAG_STRIDED) update kernel
  *   "fuse_max_params"    > 0: a tensor list of at most this many elements, all of whose blocks fit one
  *                        1024-lane team of the generic kernel, is stepped in ONE launch (a step of a small

@@ -359,7 +359,7 @@ int launch_elementwise(const AmBucket& bk, const AmTable& tab, float* v, const A
   const uint32_t grid = grid_for(bk.n_items, cx.t);
 #define X(L, U)                                                                                       \
   if (var.lanes == L && var.upt == U)                                                                 \
-    return launch_capped(am_elementwise<G, VEC, L, U>, grid, L, cx.t.stream_wg_per_cu, cx, AM_TAB,    \
+    return launch_capped(am_elementwise<G, VEC, L, U>, grid, L, cx.t.ew_wg_per_cu, cx, AM_TAB,        \
                          n_items, v, sc);
   AM_EW_VARIANTS(X)
 #undef X
@@ -750,6 +750,7 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "row_blocked") g_tuning.row_blocked = value;
   else if (k == "stream_wg_per_cu") g_tuning.stream_wg_per_cu = value;
   else if (k == "strided_wg_per_cu") g_tuning.strided_wg_per_cu = value;
+  else if (k == "ew_wg_per_cu") g_tuning.ew_wg_per_cu = value;
   else if (k == "fuse_max_params") g_tuning.fuse_max_params = value;
   else if (k == "fuse_target_items") { if (value < 1) return ADAM_MINI_INVALID_ARG; g_tuning.fuse_target_items = value; }
   else if (k == "large_slice_mb") g_tuning.large_slice_mb = value;

@@ -64,7 +64,8 @@ struct AmTuning {
   int64_t row_wg_per_cu = 0;        // > 0: fixed cap on resident row-kernel workgroups per compute unit (overrides row_inflight_kb)
   int64_t row_blocked = 0;          // 1: each wavefront of a row team owns a contiguous span of the block
   int64_t strided_wg_per_cu = 2;    // > 0: cap on resident workgroups per compute unit of the column-block update kernel
-  int64_t stream_wg_per_cu = 2;     // > 0: same for the elementwise / large-update streaming kernels
+  int64_t stream_wg_per_cu = 2;     // > 0: same for the large-block update kernel
+  int64_t ew_wg_per_cu = 2;         // > 0: same for the AdamW-equivalent (one-element-block) kernel
   int64_t fuse_max_params = 16 << 20;  // > 0: a tensor list of at most this many elements whose blocks all fit one
                                     //   team of the generic kernel is stepped in ONE launch (small models are
                                     //   bound by the number of launches); 0 = never

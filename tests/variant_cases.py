@@ -98,6 +98,8 @@ CASES = [
     ("row_wg_per_cu=3", _o(row_wg_per_cu=3), ("f32",)),
     ("row_inflight_kb=0", _o(row_inflight_kb=0), ("bf16",)),
     ("row_inflight_kb=16", _o(row_inflight_kb=16), ("f32",)),
+    ("ew_wg_per_cu=0", _o(ew_wg_per_cu=0), ("bf16",)),
+    ("ew_wg_per_cu=1", _o(ew_wg_per_cu=1), ("f32",)),
     ("stream_wg_per_cu=0", _o(stream_wg_per_cu=0), ("bf16",)),
     ("stream_wg_per_cu=1", _o(stream_wg_per_cu=1), ("f32",)),
     ("stream_wg_per_cu=8", _o(stream_wg_per_cu=8), ("bf16",)),
