@@ -39,6 +39,10 @@ def parse_args():
     ap.add_argument("--no-bucket-events", action="store_true",
                     help="do not record per-bucket HIP events inside the timed spans (two events per launch distort a "
                          "step of a few microseconds); the roofline then takes each launch's share of the step time")
+    ap.add_argument("--allocation", default="arena", choices=["arena", "per-tensor"],
+                    help="arena: params, exp_avg and grads are three flat allocations with the tensors back to back "
+                         "(each on a 4 KiB boundary), as frameworks with flat parameter and state buffers hold them; "
+                         "per-tensor: one allocation per tensor and kind.  Same kernels and launches either way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short runs of the other BASELINE configurations (reported under all_configs)")
@@ -167,7 +171,7 @@ def main():
 
     torch.cuda.set_device(0)
     _progress("%s: %d tensors, allocating" % (wl.name, len(wl.specs)))
-    run = DeviceState(wl.specs, wl.grad_dtype)
+    run = DeviceState(wl.specs, wl.grad_dtype, arena=args.allocation == "arena")
     for k, s in enumerate(wl.specs):
         run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
         workloads.fill_grad(run.g[k], s, wl, k, 1, row_chunk=8192)
@@ -254,6 +258,8 @@ def main():
         "config": {"workload": wl.name + ("_adamw" if args.adamw else "") + ("" if args.reducer == "mean" else "_" + args.reducer),
                    "params": n_params, "blocks": n_blocks,
                    "tensors": len(wl.specs), "grad_dtype": wl.grad_dtype, "state_dtype": "f32",
+                   "allocation": "three flat arenas (params, exp_avg, grads), tensors back to back on 4 KiB boundaries"
+                   if args.allocation == "arena" else "one allocation per tensor and kind",
                    "launches_per_step": sum(b["n_kernels"] for b in buckets)},
         "whole_step": {"algorithmic_GBps": round(whole_gbs, 1), "frac_of_peak": round(whole_gbs / HBM_PEAK_GBS, 4),
                        "bytes_per_param": per_param},
@@ -271,52 +277,65 @@ def main():
     del run
     default_run = args.workload == "llama2_7b" and not args.adamw and args.reducer == "mean" and not args.option
     if default_run and not args.no_other_configs:
-        out["all_configs"] = other_configs(out, torch, B, workloads, DeviceState)
+        arena = args.allocation == "arena"
+        # the same workload with the other allocation scheme, so that the effect of the memory layout is on record
+        _progress("other allocation scheme: %s" % wl.name)
+        other = short_run(torch, workloads, DeviceState, wl.name, not arena)
+        if other is not None:
+            other["allocation"] = "per-tensor" if arena else "arena"
+            out["other_allocation"] = other
+        out["all_configs"] = other_configs(out, torch, workloads, DeviceState, arena)
     print(json.dumps(out), flush=True)
 
 
-def other_configs(primary, torch, B, workloads, DeviceState):
-    """Throughput and HBM fraction of every BASELINE configuration on this GPU: the timed workload above plus, for
-    each of the others that fits the device, the median of 10 spans of at least 100 ms each, same launch configuration."""
+def short_run(torch, workloads, DeviceState, name, arena):
+    """One workload in the default launch configuration: median of 10 spans of at least 100 ms each.
+    None if it does not fit the device."""
+    wl = workloads.get(name)
+    gb = 2 if wl.grad_dtype == "bf16" else 4
+    n_params = sum(s.numel for s in wl.specs)
+    if n_params * (8 + gb + 4) + (8 << 30) > torch.cuda.get_device_properties(0).total_memory:
+        return None
+    torch.cuda.empty_cache()
+    run = DeviceState(wl.specs, wl.grad_dtype, arena=arena)
+    for k, s in enumerate(wl.specs):
+        run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
+        workloads.fill_grad(run.g[k], s, wl, k, 1, row_chunk=8192)
+    hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
+    stream = torch.cuda.current_stream().cuda_stream
+    counter = {"t": 0}
+
+    def one_step():
+        counter["t"] += 1
+        run.opt.step(step=counter["t"], stream=stream, **hp)
+
+    for _ in range(3):
+        one_step()
+    est, _ = time_spans(torch, one_step, 3, 1)                      # sizes the spans: at least 100 ms each
+    steps = max(3, int(100.0 / max(est[0] / 3, 1e-4)) + 1)
+    ev_ms, host_ms = time_spans(torch, one_step, steps, 10)
+    ms = max(median(ev_ms), median(host_ms)) / steps
+    gbs = (n_params * (16 + gb) + 8 * run.opt.num_blocks) / (ms * 1e-3) / 1e9
+    row = {"workload": name, "ms_per_step": round(ms, 5), "Gparams_per_s": round(n_params / ms / 1e6, 2),
+           "algorithmic_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+           "spans": 10, "steps_per_span": steps,
+           "ms_per_step_min": round(min(ev_ms) / steps, 5), "ms_per_step_max": round(max(host_ms) / steps, 5)}
+    run.close()
+    del run
+    torch.cuda.empty_cache()
+    return row
+
+
+def other_configs(primary, torch, workloads, DeviceState, arena):
+    """Throughput and HBM fraction of every BASELINE configuration on this GPU: the timed workload above plus
+    each of the others that fits the device, same launch configuration and allocation scheme."""
     rows = [{"workload": primary["config"]["workload"], "ms_per_step": primary["ms_per_step"],
              "Gparams_per_s": primary["value"], "algorithmic_GBps": primary["whole_step"]["algorithmic_GBps"],
              "frac_of_peak": primary["whole_step"]["frac_of_peak"]}]
-    total_mem = torch.cuda.get_device_properties(0).total_memory
     for name in ("tiny", "gpt2_small", "llama3_8b", "llama2_13b"):
-        wl = workloads.get(name)
-        gb = 2 if wl.grad_dtype == "bf16" else 4
-        n_params = sum(s.numel for s in wl.specs)
-        if n_params * (8 + gb + 4) + (8 << 30) > total_mem:
-            rows.append({"workload": name, "skipped": "does not fit this device"})
-            continue
-        torch.cuda.empty_cache()
         _progress("all_configs: %s" % name)
-        run = DeviceState(wl.specs, wl.grad_dtype)
-        for k, s in enumerate(wl.specs):
-            run.p[k].copy_(workloads.init_param(s, wl.seed, k, device=run.dev))
-            workloads.fill_grad(run.g[k], s, wl, k, 1, row_chunk=8192)
-        hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
-        stream = torch.cuda.current_stream().cuda_stream
-        counter = {"t": 0}
-
-        def one_step():
-            counter["t"] += 1
-            run.opt.step(step=counter["t"], stream=stream, **hp)
-
-        for _ in range(3):
-            one_step()
-        est, _ = time_spans(torch, one_step, 3, 1)                      # sizes the spans: at least 100 ms each
-        steps = max(3, int(100.0 / max(est[0] / 3, 1e-4)) + 1)
-        ev_ms, host_ms = time_spans(torch, one_step, steps, 10)
-        ms = max(median(ev_ms), median(host_ms)) / steps
-        gbs = (n_params * (16 + gb) + 8 * run.opt.num_blocks) / (ms * 1e-3) / 1e9
-        rows.append({"workload": name, "ms_per_step": round(ms, 5), "Gparams_per_s": round(n_params / ms / 1e6, 2),
-                     "algorithmic_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
-                     "spans": 10, "steps_per_span": steps,
-                     "ms_per_step_min": round(min(ev_ms) / steps, 5), "ms_per_step_max": round(max(host_ms) / steps, 5)})
-        run.close()
-        del run
-    torch.cuda.empty_cache()
+        row = short_run(torch, workloads, DeviceState, name, arena)
+        rows.append(row if row is not None else {"workload": name, "skipped": "does not fit this device"})
     return rows
 
 

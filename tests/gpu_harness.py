@@ -70,13 +70,13 @@ def make_specs(blocks, strided=False):
 
 
 def run_both(wl: workloads.Workload, steps=None, hp=None, mutate_grad=None, check_every_step=False,
-             gen_device="cpu", storage="f64"):
+             gen_device="cpu", storage="f64", arena=False):
     """Steps the HIP library and the oracle over the whole workload `wl` with the same
     inputs and compares p, m and v after the last step (or after every step).
     Returns (GpuRun, OracleState, worst normwise relative error)."""
     import torch
     steps = wl.steps if steps is None else steps
-    run = GpuRun(wl.specs, wl.grad_dtype)
+    run = GpuRun(wl.specs, wl.grad_dtype, arena=arena)
     p0 = []
     for k, s in enumerate(wl.specs):
         x = workloads.init_param(s, wl.seed, k, device=gen_device)
@@ -223,8 +223,9 @@ def record_error(workload: str, mode: str, worst: float, elements: int, steps: i
         pass
 
 
-def run_complete(wl: workloads.Workload, steps=None, tensors=None, progress=None, row_chunk=8192):
-    """Full-size run on the GPU over ALL tensors of `wl` (the launch configuration the benchmark times),
+def run_complete(wl: workloads.Workload, steps=None, tensors=None, progress=None, row_chunk=8192, arena=True):
+    """Full-size run on the GPU over ALL tensors of `wl` (the launch configuration and, with arena=True, the
+    allocation scheme the benchmark times; the sampled runs use one allocation per tensor),
     then the oracle streamed tensor by tensor: for each tensor in `tensors` (default: every one) the
     initial values and the gradient of every step are generated again from their seeds, the oracle steps
     that whole tensor on the host, and every element of p and m and every v of the tensor is compared.
@@ -233,7 +234,7 @@ def run_complete(wl: workloads.Workload, steps=None, tensors=None, progress=None
     import torch
     steps = wl.steps if steps is None else steps
     todo = list(range(len(wl.specs))) if tensors is None else list(tensors)
-    run = GpuRun(wl.specs, wl.grad_dtype)
+    run = GpuRun(wl.specs, wl.grad_dtype, arena=arena)
     hp = dict(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
     ohp = orc.Hyper.from_f32(**hp)
     for k, s in enumerate(wl.specs):

@@ -124,12 +124,15 @@ def test_error_splits_into_storage_rounding_and_arithmetic():
     assert errs["f64"] < 1e-5 and errs["f32"] < 1e-5
 
 
-def test_config2_gpt2_small_20_steps():
+@pytest.mark.parametrize("arena", [False, True])
+def test_config2_gpt2_small_20_steps(arena):
+    """arena: the tensors of each kind back to back in one allocation (the benchmark's scheme) or one
+    allocation per tensor; the library sees only pointers either way."""
     import gpu_harness as H
     from paper_2406_16793_amd import workloads
     wl = workloads.get("gpt2_small")
-    run, st, worst = H.run_both(wl, gen_device="cuda")
-    print("gpt2_small: worst normwise rel err %.3g" % worst, flush=True)
+    run, st, worst = H.run_both(wl, gen_device="cuda", arena=arena)
+    print("gpt2_small (arena=%s): worst normwise rel err %.3g" % (arena, worst), flush=True)
     run.close()
 
 
