@@ -223,7 +223,8 @@ int adam_mini_step_device_hparams(adam_mini_layout* layout, void* const* params,
  * ADAM_MINI_STATIC_SCRATCH_BYTES inside the library's code object (every GPU the
  * library runs on holds its own copy until the process ends), and the tables reach it
  * as arguments of small kernels on hip_stream.  The call makes no hipMalloc, no
- * hipFree, no copy and no other allocating call, on its first use or later.
+ * hipFree, no copy and no other allocating call, on its first use or later (the host
+ * staging of the tables is sized by adam_mini_init_layout).
  * A layout needs  n_tensors * 116 + (partial sums + step scales) * 4 + 256  bytes, each part
  * rounded up to 256 (partial sums: one per 4096-element chunk of every block that
  * spans several workgroups, or one per column and tile of rows for column blocks);

@@ -94,6 +94,7 @@ struct adam_mini_layout {
   AmDeviceMem mem;                 // the layout's own allocations
   AmPointerCache cache;            // pointer lists held by mem.segs
   AmPointerCache static_cache;     // pointer lists this layout last wrote into the static scratch
+  std::vector<unsigned char> static_image;  // host staging of those tables (so that entry point allocates no host memory either)
   // optional per-bucket timing: events[(step * n_buckets + bucket) * 2 + {0,1}]
   std::vector<hipEvent_t> events;
   uint32_t profile_capacity = 0;   // steps the pool can hold
@@ -539,9 +540,9 @@ AmDeviceMem carve(unsigned char* base, const AmTableBytes& b) {
 
 // Host image of the segment and key tables ([0, b.partials) of the byte layout) with the given pointer
 // lists (null lists: pointers stay null, which is enough for the id kernels).
-std::vector<unsigned char> table_image(const adam_mini_layout* L, const AmTableBytes& b, void* const* params,
-                                       const void* const* grads, void* const* exp_avg) {
-  std::vector<unsigned char> img(b.partials, 0);
+void table_image(const adam_mini_layout* L, const AmTableBytes& b, void* const* params, const void* const* grads,
+                 void* const* exp_avg, std::vector<unsigned char>& img) {
+  img.assign(b.partials, 0);  // no reallocation when the vector already has this size
   AmSeg* segs = reinterpret_cast<AmSeg*>(img.data() + b.segs);
   uint32_t* keys = reinterpret_cast<uint32_t*>(img.data() + b.keys);
   const size_t n = L->host.n_segs;
@@ -558,7 +559,6 @@ std::vector<unsigned char> table_image(const adam_mini_layout* L, const AmTableB
       keys[n + bk.table_offset + i] = s.lblock_first;
       keys[2 * n + bk.table_offset + i] = i < bk.item2_first.size() ? bk.item2_first[i] : 0u;
     }
-  return img;
 }
 
 void free_device_state(adam_mini_layout* L) {
@@ -582,7 +582,8 @@ int allocate_device_state(adam_mini_layout* L) {
   AM_HIP(hipMalloc((void**)&base, b.total));
   L->mem = carve(base, b);
   // the tables without data pointers; a step fills those in with am_write_pointers
-  const std::vector<unsigned char> img = table_image(L, b, nullptr, nullptr, nullptr);
+  std::vector<unsigned char> img;
+  table_image(L, b, nullptr, nullptr, nullptr, img);
   AM_HIP(hipMemcpy(base, img.data(), img.size(), hipMemcpyHostToDevice));
   const int rc = query_device(L);
   if (rc == ADAM_MINI_OK) L->lds_per_cu_known = true;
@@ -793,6 +794,8 @@ int adam_mini_init_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors
         c->g.assign(n_tensors, nullptr);
         c->m.assign(n_tensors, nullptr);
       }
+      const AmTableBytes b = table_bytes(L->host);
+      if (b.total <= (size_t)ADAM_MINI_STATIC_SCRATCH_BYTES) L->static_image.assign(b.partials, 0);
     }
   } catch (const std::bad_alloc&) {
     rc = ADAM_MINI_OUT_OF_MEMORY;
@@ -933,11 +936,8 @@ int adam_mini_step_static(adam_mini_layout* layout, void* const* params, const v
   if (g_scratch_owner[layout->device] != layout->uid || !layout->static_cache.same(params, grads, exp_avg, n)) {
     g_scratch_owner[layout->device] = 0;
     layout->static_cache.valid = false;
-    try {
-      rc = write_image(base, table_image(layout, b, params, grads, exp_avg), stream);
-    } catch (const std::bad_alloc&) {
-      rc = ADAM_MINI_OUT_OF_MEMORY;
-    }
+    table_image(layout, b, params, grads, exp_avg, layout->static_image);  // sized by adam_mini_init_layout
+    rc = write_image(base, layout->static_image, stream);
     if (rc != ADAM_MINI_OK) return rc;
     layout->static_cache.keep(params, grads, exp_avg, n);
     g_scratch_owner[layout->device] = layout->uid;
