@@ -293,6 +293,10 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *   "max_upt"            preferred bound on units per thread; the smallest team within it is used
  *   "row_max_units"      blocks above this leave the single-pass register kernel
  *   "lds_max_bytes"      > 0: such blocks whose gradient fits in this much LDS use the LDS-staged kernel
+ *   "cu_count"           compute units assumed when deciding whether the LDS-staged kernel (one workgroup per
+ *                        block) pays: a list with more staged blocks than this whose last round of workgroups
+ *                        would be mostly empty (under 80 % filled on average with bf16 gradients, 55 % with
+ *                        fp32) uses the multi-workgroup path for them instead; default 256, 0 = always stage
  *   "large_chunk_upt"    units per thread of a chunk in the multi-workgroup path (1, 2, 4, 8, 16)
  *   "large_slice_mb"     > 0: the multi-workgroup bucket is cut at block boundaries into slices of at most this
  *                        many MB of gradient, each running its three kernels back to back (a measurement knob:

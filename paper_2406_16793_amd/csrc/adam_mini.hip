@@ -743,6 +743,7 @@ int adam_mini_set_option(const char* key, int64_t value) {
     if (value > (int64_t)(kLdsPerCuMax - kCapSlackBytes)) return ADAM_MINI_INVALID_ARG;
     g_tuning.lds_max_bytes = value;
   }
+  else if (k == "cu_count") g_tuning.cu_count = value;
   else if (k == "large_chunk_upt") g_tuning.large_chunk_upt = value;
   else if (k == "ew_upt") g_tuning.ew_upt = value;
   else if (k == "grid_cap") g_tuning.grid_cap = value;

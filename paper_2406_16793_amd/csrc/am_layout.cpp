@@ -143,6 +143,23 @@ AmVariant am_choose_variant(int grad_dtype, uint64_t numel, uint64_t block_numel
   return var;
 }
 
+// The LDS-staged kernel runs ONE workgroup per block and a compute unit holds one or two of them, so its
+// launch proceeds in rounds of cu_count workgroups.  With n staged blocks in the list, the last round is
+// n - (rounds - 1) * cu_count workgroups wide and the others wait for it: at 288 blocks of 96 KB (the
+// query/key heads of a 12-layer, 12-head model with bf16 gradients) the staged kernel takes 22 % longer
+// than partial sums / finalize / update, which spread every block over several workgroups, at 256 or
+// 512 blocks it is equal or faster.  Staging saves the second read of the gradient: 4 of 24 bytes per
+// element with fp32 gradients, 2 of 20 with bf16, so fp32 lists tolerate a worse balance (measured:
+// still 2 to 8 % ahead at 288 and 384 blocks).  Lists with fewer staged blocks than compute units
+// run in one round and are left alone.
+bool am_staging_pays(int grad_dtype, uint64_t n_staged_blocks, const AmTuning& t) {
+  if (t.cu_count <= 0 || n_staged_blocks <= (uint64_t)t.cu_count) return true;
+  const uint64_t cu = (uint64_t)t.cu_count;
+  const uint64_t rounds = (n_staged_blocks + cu - 1) / cu;
+  const double balance = (double)n_staged_blocks / (double)(rounds * cu);
+  return balance >= (grad_dtype == ADAM_MINI_GRAD_BF16 ? 0.8 : 0.55);
+}
+
 // A small list goes through the one-launch generic kernel when every tensor fits it -- contiguous blocks of
 // whole 4-element units that one 1024-lane team can hold, or one-element blocks in whole units with a
 // 16-byte aligned v slice -- and when that saves launches, i.e. the tuned kernels would need more than one.
@@ -181,6 +198,21 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
   out->tensors.clear();
   out->buckets.clear();
   const bool fused = am_list_is_fusable(grad_dtype, descs, n_tensors, tuning);
+  // variant choice per tensor, with LDS staging switched off for the whole list where it would not pay
+  AmTuning choice = tuning;
+  if (!fused && tuning.lds_max_bytes > 0) {
+    uint64_t n_staged = 0, v_at = 0;
+    for (uint32_t k = 0; k < n_tensors; ++k) {
+      const adam_mini_tensor_desc& d = descs[k];
+      if (d.numel == 0 || d.block_numel == 0 || d.numel % d.block_numel != 0) return ADAM_MINI_INVALID_ARG;
+      const uint64_t n_blocks = d.numel / d.block_numel;
+      const bool strided = (d.flags & ADAM_MINI_FLAG_STRIDED) != 0 && n_blocks > 1 && d.block_numel > 1;
+      if (!strided && am_choose_variant(grad_dtype, d.numel, d.block_numel, v_at, tuning).family == AM_FAM_ROW_LDS)
+        n_staged += n_blocks;
+      v_at += n_blocks;
+    }
+    if (!am_staging_pays(grad_dtype, n_staged, tuning)) choice.lds_max_bytes = 0;
+  }
   uint64_t fused_item_bytes = 0;
   if (fused) {
     uint64_t total = 0;
@@ -226,7 +258,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       // read-only partial pass can take a lane's 8 gradients in one 128-bit load
       var.aux = (grad_dtype == ADAM_MINI_GRAD_BF16 && var.vec == 4 && ti.n_blocks % 8 == 0) ? 2 : 1;
     } else {
-      var = am_choose_variant(grad_dtype, d.numel, d.block_numel, ti.v_first, tuning);
+      var = am_choose_variant(grad_dtype, d.numel, d.block_numel, ti.v_first, choice);
     }
     int b = -1;
     for (size_t i = 0; i < out->buckets.size(); ++i)

@@ -53,6 +53,10 @@ struct AmTuning {
   int64_t row_max_units = 1 << 30;  // blocks above this never use the single-pass register kernel
   int64_t lds_max_bytes = 150 * 1024;       // > 0: blocks that do not fit the register kernel and whose gradient fits
                                     //      in this many bytes of LDS use the LDS-staged single-pass kernel
+  int64_t cu_count = 256;           // compute units the LDS-staged kernel's workgroups (one per block, one or two per
+                                    //   unit) are dealt to: a list whose staged blocks fill their last round of
+                                    //   workgroups badly sends them to the multi-workgroup kernels instead
+                                    //   (am_staging_pays in am_layout.cpp); 0 = never mind the balance
   int64_t large_chunk_upt = 4;      // LARGE: units per thread of a 256-thread chunk (1, 2, 4, 8 or 16)
   int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (1, 2, 4 or 8)
   int64_t large_slice_mb = 0;       // LARGE: > 0 cuts the bucket into slices of at most this many MB of gradient,

@@ -14,6 +14,8 @@ OUT_DIR = os.environ.get("ADAM_MINI_TEST_OUT", os.path.join(ROOT, "gpurun_out"))
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # used by the full-size tests; registered here too so that it is known where pytest-timeout is not installed
+    config.addinivalue_line("markers", "timeout: per-test time limit (pytest-timeout)")
 
 
 @pytest.fixture(scope="session")

@@ -56,6 +56,43 @@ def assert_state_close(name, got, want, rtol, is_v=False, block_numel=None, stri
     return float(np.linalg.norm(d) / denom) if denom > 0 else 0.0
 
 
+def assert_state_close_on_device(name, got, want, rtol, is_v=False, block_numel=None, strided=False):
+    """assert_state_close for arrays of 10^8 elements: the same bound and the same return value, evaluated
+    in float64 by PyTorch on the GPU that already holds `got` (a device tensor); `want` is the oracle's
+    host array.  Only the comparison runs there; the expected values are the oracle's."""
+    import torch
+    rtol = check_rtol(rtol)
+    want = torch.from_numpy(np.ascontiguousarray(want, dtype=np.float64)).to(got.device)
+    got = got.to(torch.float64)
+    assert got.shape == want.shape, name
+    ok = torch.isfinite(want)
+    assert torch.equal(torch.isfinite(got), ok), "%s: non-finite pattern differs" % name
+    zero = torch.zeros((), dtype=torch.float64, device=got.device)
+    w = torch.where(ok, want, zero)
+    d = torch.where(ok, got - want, zero)
+    if is_v:
+        tol = rtol * w.abs() + 1e-30
+    elif block_numel is not None and block_numel > 1 and w.numel() % block_numel == 0:
+        n_blocks = w.numel() // block_numel
+        shape, axis = ((block_numel, n_blocks), 0) if strided else ((n_blocks, block_numel), 1)
+        w2, ok2 = w.reshape(shape), ok.reshape(shape)
+        count = ok2.sum(dim=axis, keepdim=True).clamp(min=1).to(torch.float64)
+        rms = torch.sqrt(w2.square().sum(dim=axis, keepdim=True) / count)
+        tol = (rtol * w2.abs() + rtol * rms).reshape(-1)
+    else:
+        rms = float(torch.sqrt(w.square().sum() / max(1, int(ok.sum()))))
+        tol = rtol * w.abs() + rtol * rms
+    err = d.abs()
+    bad = err > tol
+    if bool(bad.any()):
+        i = int(torch.argmax(err - tol))
+        raise AssertionError("%s: %d of %d elements off; worst idx %d got %.9g want %.9g err %.3g tol %.3g"
+                             % (name, int(bad.sum()), got.numel(), i, float(got[i]), float(want[i]), float(err[i]),
+                                float(tol[i])))
+    denom = float(torch.linalg.vector_norm(w))
+    return float(torch.linalg.vector_norm(d)) / denom if denom > 0 else 0.0
+
+
 def make_specs(blocks, strided=False):
     """blocks: list of (n_blocks, block_numel[, wd_scale]) -> TensorSpec list.  strided: the tensors
     are stored [block_numel, n_blocks] and their blocks are the columns."""
@@ -264,10 +301,10 @@ def run_complete(wl: workloads.Workload, steps=None, tensors=None, progress=None
         del tmp
         name = "%s[%d] %s" % (wl.name, k, s.name)
         bn = dict(block_numel=s.block_numel, strided=s.strided)
-        worst = max(worst, assert_state_close("param " + name, run.p[k].cpu().numpy(), st.p[0], wl.rtol, **bn))
-        worst = max(worst, assert_state_close("m " + name, run.m[k].cpu().numpy(), st.m[0], wl.rtol, **bn))
-        vk = run.v[int(v_first[k]):int(v_first[k + 1])].cpu().numpy()
-        worst = max(worst, assert_state_close("v " + name, vk, st.v[0], wl.rtol, is_v=True))
+        worst = max(worst, assert_state_close_on_device("param " + name, run.p[k], st.p[0], wl.rtol, **bn))
+        worst = max(worst, assert_state_close_on_device("m " + name, run.m[k], st.m[0], wl.rtol, **bn))
+        vk = run.v[int(v_first[k]):int(v_first[k + 1])]
+        worst = max(worst, assert_state_close_on_device("v " + name, vk, st.v[0], wl.rtol, is_v=True))
         compared += 2 * s.numel + s.n_blocks
         since += s.numel
         del st

@@ -311,6 +311,33 @@ def test_small_lists_take_one_launch_only_when_that_saves_launches():
         B.adam_mini_set_option("reset", 0)
 
 
+def test_lds_staging_is_dropped_where_its_last_round_of_workgroups_would_be_mostly_empty():
+    """One workgroup per staged block: 288 blocks on 256 compute units leave the second round 12 % full."""
+    def kinds(descs, dtype):
+        h = B.adam_mini_init_layout(descs, dtype, -1)
+        out = B.adam_mini_export_layout(h)[1]
+        B.adam_mini_destroy_layout(h)
+        return out
+    head = 64 * 768                                   # 96 KB of bf16 gradient: beyond the registers, within the LDS
+    qk = lambda n: [(12 * head, head, 1.0)] * (n // 12)
+    rows = (4096 * 768, 768, 1.0)
+    assert kinds(qk(288) + [rows], B.GRAD_BF16) == [B.PATH_LARGE] * 24 + [B.PATH_ROW]
+    assert kinds(qk(240) + [rows], B.GRAD_BF16) == [B.PATH_ROW_LDS] * 20 + [B.PATH_ROW]      # a single round
+    assert kinds(qk(504), B.GRAD_BF16) == [B.PATH_ROW_LDS] * 42                              # 504 / 512
+    assert kinds(qk(384), B.GRAD_BF16) == [B.PATH_LARGE] * 32                                # 384 / 512
+    assert kinds(qk(2340), B.GRAD_BF16) == [B.PATH_ROW_LDS] * 195                            # 2340 / 2560
+    small = 64 * 512                                  # 128 KB of fp32 gradient
+    assert kinds([(12 * small, small, 1.0)] * 24, B.GRAD_F32) == [B.PATH_ROW_LDS] * 24       # 288 / 512 is enough with fp32
+    assert kinds([(small, small, 1.0)] * 260, B.GRAD_F32) == [B.PATH_LARGE] * 260            # 260 / 512 is not
+    B.adam_mini_set_option("cu_count", 0)
+    try:
+        assert kinds(qk(288), B.GRAD_BF16) == [B.PATH_ROW_LDS] * 24
+        B.adam_mini_set_option("cu_count", 96)
+        assert kinds(qk(288), B.GRAD_BF16) == [B.PATH_ROW_LDS] * 24                          # three full rounds
+    finally:
+        B.adam_mini_set_option("reset", 0)
+
+
 def test_device_hparams_step_validates_on_the_host_what_it_can():
     h = B.adam_mini_init_layout([(16, 4, 1.0)], B.GRAD_F32, -1)
     lib = B.load()

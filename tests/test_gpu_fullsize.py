@@ -10,7 +10,8 @@ comparison asserts a normwise relative error below 1e-5 next to the elementwise 
 worst figure in fullsize_errors.json in the run's output folder."""
 import pytest
 
-pytestmark = pytest.mark.gpu
+# minutes, not seconds, per test: a per-test time limit given on the command line must not cut them short
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1200)]
 
 
 def _fits(torch, need):

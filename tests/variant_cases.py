@@ -93,6 +93,9 @@ CASES = [
     ("row_max_units=1024-no-lds", _o(row_max_units=1024, lds_max_bytes=0), BOTH),
     ("lds_max_bytes=0", _o(lds_max_bytes=0), BOTH),
     ("lds_max_bytes=100K", _o(lds_max_bytes=100 * 1024), BOTH),
+    ("cu_count=4", _o(cu_count=4), BOTH),          # 6 staged blocks on "4 compute units": badly balanced, not staged
+    ("cu_count=3", _o(cu_count=3), BOTH),          # two full rounds: staged
+    ("cu_count=0", _o(cu_count=0), ("bf16",)),     # balance never considered
     # occupancy caps (dynamic LDS the kernels never touch) and XCD run lengths: launch shape only
     ("row_wg_per_cu=1", _o(row_wg_per_cu=1), ("bf16",)),
     ("row_wg_per_cu=3", _o(row_wg_per_cu=3), ("f32",)),
