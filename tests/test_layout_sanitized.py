@@ -17,14 +17,15 @@ def test_layout_builder_under_address_and_ub_sanitizers(tmp_path):
     if gxx is None:
         pytest.skip("no g++")
     exe = str(tmp_path / "layout_sanitize")
+    # the sanitizer runtimes are linked statically: the program then does not depend on being the first
+    # library the loader sees, whatever else the environment loads into a process
     cmd = [gxx, "-std=c++17", "-O1", "-g", "-Wall", "-Wextra", "-fsanitize=address,undefined",
-           "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           "-static-libasan", "-static-libubsan", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
            os.path.join(ROOT, "tests", "layout_sanitize.cpp"),
            os.path.join(ROOT, "paper_2406_16793_amd", "csrc", "am_layout.cpp"), "-o", exe]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
     assert res.returncode == 0, res.stdout
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
-    env.pop("LD_PRELOAD", None)      # the sanitizer runtime must come first in the new process
     run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300, env=env)
     assert run.returncode == 0, run.stdout[-4000:]
     assert "layout checks passed" in run.stdout
