@@ -352,3 +352,45 @@ def test_device_hparams_step_validates_on_the_host_what_it_can():
     assert call(None, 0x1000, 0x2000, 1) == B.INVALID_ARG
     B.adam_mini_destroy_layout(h)
     assert ctypes.sizeof(B.HParams) == 32
+
+
+def test_header_is_plain_c_and_a_c_client_links(tmp_path):
+    """include/adam_mini.h is the boundary: it must compile as C99 and as C++11 on its own, and a C program
+    that uses nothing else must link against the library and run its host-only calls."""
+    import shutil
+    import subprocess
+    gcc, gxx = shutil.which("gcc"), shutil.which("g++")
+    if gcc is None or gxx is None:
+        pytest.skip("no gcc / g++")
+    header = os.path.join(ROOT, "include", "adam_mini.h")
+    for cc, std, lang in ((gcc, "-std=c99", "c"), (gxx, "-std=c++11", "c++")):
+        res = subprocess.run([cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", lang, header],
+                             stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert res.returncode == 0, res.stdout
+    src = tmp_path / "client.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "adam_mini.h"
+int main(void) {
+  adam_mini_tensor_desc d[2] = {{4096u * 8u, 4096u, 1.0f, 0u}, {256u, 256u, 0.0f, 0u}};
+  adam_mini_layout* L = 0;
+  uint64_t off[3], id = 0;
+  uint32_t kind[2];
+  if (adam_mini_init_layout(d, 2, ADAM_MINI_GRAD_BF16, -1, &L) != ADAM_MINI_OK) return 1;
+  if (adam_mini_num_blocks(L) != 9 || adam_mini_num_tensors(L) != 2) return 2;
+  if (adam_mini_export_layout(L, off, kind) != ADAM_MINI_OK || off[1] != 8 || off[2] != 9) return 3;
+  if (adam_mini_block_id(L, 0, 4096u * 3u + 5u, &id) != ADAM_MINI_OK || id != 3) return 4;
+  if (adam_mini_init_layout(d, 0, ADAM_MINI_GRAD_BF16, -1, &L) != ADAM_MINI_INVALID_ARG) return 5;
+  printf("%s\n", adam_mini_strerror(ADAM_MINI_MISALIGNED));
+  return 0;
+}
+''')
+    exe = str(tmp_path / "client")
+    libdir = os.path.dirname(B.LIB_PATH)
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-I", os.path.join(ROOT, "include"), str(src), "-o", exe,
+                          "-L", libdir, "-ladam_mini", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"],
+                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert run.returncode == 0, (run.returncode, run.stdout)
+    assert "16-byte aligned" in run.stdout
