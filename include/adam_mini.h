@@ -108,7 +108,7 @@ typedef struct adam_mini_tensor_desc {
   uint32_t flags;       /* ADAM_MINI_FLAG_STRIDED and / or one ADAM_MINI_REDUCE_*; other bits are reserved and must be 0 */
 } adam_mini_tensor_desc;
 
-/* Hyper-parameters of one step (Algorithm 1, lines 1 and 5-10). */
+/* Hyper-parameters of one step (the inputs of Algorithm 1 and its step counter t). */
 typedef struct adam_mini_hparams {
   float lr;           /* eta_t, finite */
   float beta1;        /* in [0,1) */
@@ -167,7 +167,7 @@ int adam_mini_write_block_ids(adam_mini_layout* layout, uint32_t tensor,
                               uint64_t* ids_dev, void* hip_stream);
 
 /*
- * One optimizer step over all tensors (Algorithm 1 lines 3-11 for every block).
+ * One optimizer step over all tensors (the body of Algorithm 1's loop, for every block).
  *   params   host array [n_tensors] of device pointers, fp32, updated in place
  *   grads    host array [n_tensors] of device pointers, fp32 or bf16 per the layout; read only
  *   exp_avg  host array [n_tensors] of device pointers, fp32 first moment m, updated in place
