@@ -302,6 +302,9 @@ int adam_mini_profile_read(adam_mini_layout* layout, adam_mini_bucket_info* out,
  *                        many MB of gradient, each running its three kernels back to back (a measurement knob:
  *                        every extra launch costs about 4 us and the second gradient read is not served on
  *                        chip, so the default 0, one slice, is fastest)
+ *   "large_wide_chunks"  a multi-workgroup bucket with a block of at least this many chunks (whole-tensor blocks)
+ *                        sums each block's chunk partials with one 1024-thread workgroup instead of one
+ *                        wavefront; default 512, 0 = never
  *   "large_keep_g"       1: the multi-workgroup kernels read the gradient with ordinary cached loads instead of
  *                        streaming ones (a measurement knob; no effect seen)
  *   "ew_upt"             units per thread of a tile in the AdamW-equivalent kernel (1, 2, 4, 8)

@@ -310,6 +310,8 @@ int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScala
   float* partials = cx.mem.partials;
   float* scales = cx.mem.scales;
   const uint32_t keep_g = cx.t.large_keep_g != 0;  // ordinary cached gradient loads instead of streaming ones
+  // blocks of very many chunks: a workgroup instead of a wavefront sums each block's partials
+  const bool wide = cx.t.large_wide_chunks > 0 && bk.max_chunks >= (uint64_t)cx.t.large_wide_chunks;
 #define X(L, U)                                                                                           \
   if constexpr (VEC * U <= 64) { /* larger chunks are never chosen: they would not fit the registers */   \
     if (var.lanes == L && var.upt == U) {                                                                 \
@@ -323,8 +325,13 @@ int launch_large(const AmBucket& bk, const AmTable& tab, float* v, const AmScala
         else                                                                                              \
           hipLaunchKernelGGL((am_large_partial<G, VEC, L, U, false>), dim3(pgrid), dim3(256), 0,          \
                              cx.stream, AM_TAB, sl.item_first, sl.n_items, keep_g, partials);             \
-        hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, cx.stream, AM_TAB,               \
-                           sl.lblock_first, sl.n_lblocks, (const float*)partials, v, scales, sc);         \
+        if (wide)                                                                                         \
+          hipLaunchKernelGGL(am_large_finalize_wide, dim3(grid_for(sl.n_lblocks, cx.t)),                  \
+                             dim3(kWideFinalizeThreads), 0, cx.stream, AM_TAB, sl.lblock_first,           \
+                             sl.n_lblocks, (const float*)partials, v, scales, sc);                        \
+        else                                                                                              \
+          hipLaunchKernelGGL(am_large_finalize, dim3(fgrid), dim3(256), 0, cx.stream, AM_TAB,             \
+                             sl.lblock_first, sl.n_lblocks, (const float*)partials, v, scales, sc);       \
         const int rc = launch_capped(am_large_update<G, VEC, L, U>, grid, L, cx.t.stream_wg_per_cu, cx,   \
                                      AM_TAB, sl.item_first, sl.n_items, keep_g, (const float*)scales, sc); \
         if (rc != ADAM_MINI_OK) return rc;                                                                \
@@ -757,6 +764,7 @@ int adam_mini_set_option(const char* key, int64_t value) {
   else if (k == "fuse_target_items") { if (value < 1) return ADAM_MINI_INVALID_ARG; g_tuning.fuse_target_items = value; }
   else if (k == "large_slice_mb") g_tuning.large_slice_mb = value;
   else if (k == "large_keep_g") g_tuning.large_keep_g = value;
+  else if (k == "large_wide_chunks") g_tuning.large_wide_chunks = value;
   else if (k == "strided_rows") {
     if (value < 4 || value > 65536 || value % 4 != 0) return ADAM_MINI_INVALID_ARG;
     g_tuning.strided_rows = value;

@@ -758,6 +758,54 @@ __global__ __launch_bounds__(256) void am_large_finalize(AM_KERNEL_PARAMS, uint3
   }
 }
 
+// The same for blocks cut into MANY chunks (whole-tensor blocks of 10^7..10^8 elements have 10^3..10^5 chunk
+// partials; one wavefront per block then spends longer on this walk than the update pass spends on a gigabyte):
+// one 1024-thread workgroup per block, each thread summing every 1024th partial in double, then the
+// wavefront butterfly, then the 16 wavefront results in wavefront order.  Fixed order, no atomics.
+constexpr int kWideFinalizeThreads = 1024;
+__global__ __launch_bounds__(kWideFinalizeThreads) void am_large_finalize_wide(
+    AM_KERNEL_PARAMS, uint32_t lblock_base, uint32_t n_lblocks, const float* __restrict__ partials,
+    float* __restrict__ v, float* __restrict__ scales, AmScalarsArg sc_arg) {
+  const AmScalars sc = am_scalars(sc_arg);
+  constexpr int WAVES = kWideFinalizeThreads / 64;
+  __shared__ double xch[WAVES];
+  for (uint32_t i = blockIdx.x; i < n_lblocks; i += gridDim.x) {
+    if (i != blockIdx.x) __syncthreads();  // the previous block's wavefront results have been read
+    const uint32_t lb = lblock_base + i;
+    const uint32_t s = am_find_seg(lblock_keys, n_segs, lb);
+    const AmSeg& S = segs[s];
+    const uint32_t block = lb - lblock_keys[s];
+    const uint32_t first = item_keys[s] + block * S.chunks_per_block;
+    const uint32_t red = S.reducer;
+    double acc = (double)am_red_identity(red);
+    if (am_red_is_sum_sq(red)) {
+#pragma unroll 4
+      for (uint32_t c = threadIdx.x; c < S.chunks_per_block; c += kWideFinalizeThreads) acc += (double)partials[first + c];
+      acc = am_wave_sum_f64(acc);
+    } else {
+#pragma unroll 4
+      for (uint32_t c = threadIdx.x; c < S.chunks_per_block; c += kWideFinalizeThreads)
+        acc = am_combine(red, acc, (double)partials[first + c]);
+      acc = am_wave_reduce_f64(red, acc);
+    }
+    if ((threadIdx.x & 63) == 0) xch[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double total = xch[0];
+      if (am_red_is_sum_sq(red)) {
+        for (int w = 1; w < WAVES; ++w) total += xch[w];
+      } else {
+        for (int w = 1; w < WAVES; ++w) total = am_combine(red, total, xch[w]);
+      }
+      const uint64_t v_idx = S.v_first + block;
+      float v_new, scale;
+      am_block_scalars(am_red_finish(red, (float)total, (float)S.block_numel), v[v_idx], sc, &v_new, &scale);
+      v[v_idx] = v_new;
+      scales[lb] = scale;
+    }
+  }
+}
+
 template <typename G, int VEC, int THREADS, int UPT>
 __global__ __launch_bounds__(THREADS) void am_large_update(AM_KERNEL_PARAMS, uint32_t item_base,
                                                            uint32_t n_items, uint32_t keep_g,

@@ -336,6 +336,7 @@ int am_build_layout(const adam_mini_tensor_desc* descs, uint32_t n_tensors, int 
       const uint64_t cpb = (s.units_per_block + am_tile_units(var) - 1) / am_tile_units(var);
       if (cpb >= (1ull << 31)) return ADAM_MINI_INVALID_ARG;
       s.chunks_per_block = (uint32_t)cpb;
+      if (cpb > bk.max_chunks) bk.max_chunks = cpb;
       items = ti.n_blocks * cpb;
       bk.n_lblocks += ti.n_blocks;
     }

@@ -37,6 +37,7 @@ struct AmBucket {
   uint64_t n_partials = 0;  // STRIDED: floats of partial sums the bucket needs
   uint64_t table_offset = 0;  // index of segs[0] in the concatenated device table
   uint64_t lds_bytes = 0;     // ROW_LDS: bytes of LDS that hold the largest block's gradient
+  uint64_t max_chunks = 0;    // LARGE: chunks of the bucket's largest block
   std::vector<AmSlice> slices;  // LARGE: the bucket as one slice, or cut by large_slice_mb (see am_layout.cpp)
   bool alt_reducer = false;   // some tensor's block statistic is not a plain sum of squares (2-norm, max, min)
 };
@@ -61,6 +62,8 @@ struct AmTuning {
   int64_t ew_upt = 4;               // ELEMENTWISE: units per thread of a 256-thread tile (1, 2, 4 or 8)
   int64_t large_slice_mb = 0;       // LARGE: > 0 cuts the bucket into slices of at most this many MB of gradient,
                                     //   each running partial sums, finalize and update back to back; 0 = one slice
+  int64_t large_wide_chunks = 512;  // LARGE: a bucket with a block of at least this many chunks sums each block's
+                                    //   chunk partials with a 1024-thread workgroup instead of one wavefront; 0 = never
   int64_t large_keep_g = 0;         // LARGE: 1 = the gradient is read with ordinary cached loads in both passes
   int64_t grid_cap = 0;             // > 0: at most this many workgroups per launch (grid-stride beyond)
   int64_t row_inflight_kb = 80;     // row kernel: resident workgroups per compute unit are capped so that the

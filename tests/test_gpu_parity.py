@@ -408,20 +408,27 @@ def _reducer_specs(reducers):
             for i, s in enumerate(specs)]
 
 
+@pytest.mark.parametrize("wide_finalize", [False, True])
 @pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("reducer", ["norm1", "norm2", "max", "min", "mixed"])
-def test_alternative_block_statistics(reducer, grad_dtype):
+def test_alternative_block_statistics(reducer, grad_dtype, wide_finalize):
     """The ablation's candidates for the block statistic (appendix, "Ablation Studies on the Design of
     Adam-mini"): r(g*g) with r = 1-norm, 2-norm, max, min in the v line of Algorithm 1, against the
     oracle's statement of the same reading.  "mixed" gives neighbouring tensors different statistics,
-    so 16-lane teams of one wavefront differ."""
+    so 16-lane teams of one wavefront differ.  wide_finalize: the multi-workgroup blocks' chunk
+    statistics are combined by a workgroup per block (the form whole-tensor blocks use) instead of a wavefront."""
     import gpu_harness as H
-    from paper_2406_16793_amd import workloads
+    from paper_2406_16793_amd import binding as B, workloads
     reducers = ["mean", "max", "norm2", "min", "norm1"] if reducer == "mixed" else [reducer]
     specs = _reducer_specs(reducers)
     rtol = 5e-3 if grad_dtype == "bf16" else 1e-5
     wl = workloads.Workload("reducers", 94, specs, grad_dtype, 3, rtol=rtol, zero_row_prob=0.2, zero_row_tensors=(3, 9))
-    run, st, worst = H.run_both(wl, check_every_step=True)
+    try:
+        if wide_finalize:
+            B.adam_mini_set_option("large_wide_chunks", 1)
+        run, st, worst = H.run_both(wl, check_every_step=True)
+    finally:
+        B.adam_mini_set_option("reset", 0)
     print("%s: worst normwise rel err %.3g" % (reducer, worst), flush=True)
     assert worst < 1e-5
     run.close()

@@ -70,6 +70,9 @@ CASES = [
     ("large_slice_mb=1", _o(large_slice_mb=1), BOTH),               # the multi-workgroup bucket in several slices
     ("large_slice_mb=2-keep", _o(large_slice_mb=2, large_keep_g=1, grid_cap=3, large_chunk_upt=2), BOTH),
     ("large_keep_g", _o(large_keep_g=1), ("bf16",)),
+    ("large_wide_chunks=1", _o(large_wide_chunks=1), BOTH),         # a workgroup per block sums the chunk partials
+    ("large_wide_chunks=1-small-chunks", _o(large_wide_chunks=1, large_chunk_upt=1, grid_cap=2), BOTH),
+    ("large_wide_chunks=0", _o(large_wide_chunks=0), ("f32",)),
     ("ew_upt=1", _o(ew_upt=1), BOTH),
     ("ew_upt=2", _o(ew_upt=2), BOTH),
     ("ew_upt=8", _o(ew_upt=8), BOTH),
